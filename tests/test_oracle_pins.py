@@ -1,0 +1,357 @@
+"""Pins for the fp64 CPU oracle: everything the paper and the mathematics fix
+about the MSLA module (Section 3.1, Eqs. (1)-(3), Fig. 2 right), checked with
+code that does not go through the oracle's own formulas: hand-worked values,
+the quadratic definition, invariants, library routines (numpy matmul / einsum,
+scipy correlate2d) and brute-force recomposition on tiny inputs."""
+import os
+
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+from oracle import msla_oracle as orc
+from paper_2205_14756_amd import workloads as wk
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    rows = {}
+    plain = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            try:
+                plain.append([float(p) for p in parts])
+            except ValueError:
+                rows[parts[0]] = np.array([float(p) for p in parts[1:]])
+    return rows, np.array(plain)
+
+
+def _pack(Q, K, V):
+    """[heads, N, d] x3 -> [N, 3*heads*d] in the (h, t, e) channel order."""
+    heads, N, d = Q.shape
+    m = np.empty((N, heads, 3, d))
+    m[:, :, 0] = Q.transpose(1, 0, 2)
+    m[:, :, 1] = K.transpose(1, 0, 2)
+    m[:, :, 2] = V.transpose(1, 0, 2)
+    return m.reshape(N, 3 * heads * d)
+
+
+# ----------------------------------------------------------------- Eq. (1)-(3)
+
+def test_hand_worked_example_eq3():
+    rows, _ = _golden("relu_attention_n2_d2.txt")
+    Q = rows["Q"].reshape(1, 2, 2); K = rows["K"].reshape(1, 2, 2); V = rows["V"].reshape(1, 2, 2)
+    tok = _pack(Q, K, V)
+    kv = orc.kv_state(tok, 1, 2)
+    assert np.array_equal(kv.reshape(2, 3), rows["KV"].reshape(2, 3))
+    out = orc.apply(tok, kv, 0.0)
+    assert np.allclose(out, rows["O"].reshape(2, 2), rtol=0, atol=1e-15)
+    assert np.allclose(orc.attention_nxn(Q[0], K[0], V[0], 0.0), rows["O"].reshape(2, 2),
+                       rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("N,d,heads", [(1, 16, 1), (7, 16, 3), (64, 16, 2), (33, 8, 2), (50, 4, 5)])
+def test_linear_form_equals_quadratic_form(N, d, heads):
+    rng = np.random.default_rng(N * 100 + d)
+    Q, K, V = (rng.standard_normal((heads, N, d)) for _ in range(3))
+    lin = orc.relu_linear_attention(_pack(Q, K, V), heads, d, 1e-15)
+    for h in range(heads):
+        quad = orc.attention_nxn(Q[h], K[h], V[h], 1e-15)
+        # independent numpy statement of Eq. (1)+(2) as well
+        s = np.maximum(Q[h], 0) @ np.maximum(K[h], 0).T
+        ref = (s @ V[h]) / (s.sum(1, keepdims=True) + 1e-15)
+        assert np.allclose(quad, ref, rtol=1e-12, atol=1e-13)
+        assert np.allclose(lin[:, h * d:(h + 1) * d], ref, rtol=1e-11, atol=1e-12)
+
+
+def test_kv_state_is_the_d_by_d_plus_1_sum():
+    rng = np.random.default_rng(5)
+    heads, N, d = 3, 40, 16
+    Q, K, V = (rng.standard_normal((heads, N, d)) for _ in range(3))
+    kv = orc.kv_state(_pack(Q, K, V), heads, d)
+    assert kv.shape == (heads, d, d + 1)
+    for h in range(heads):
+        rk = np.maximum(K[h], 0)
+        assert np.allclose(kv[h, :, :d], rk.T @ V[h], rtol=1e-12, atol=1e-12)
+        assert np.allclose(kv[h, :, d], rk.sum(0), rtol=1e-12, atol=1e-12)
+    # Q must not enter the state; V must not be rectified
+    kv2 = orc.kv_state(_pack(Q * 3 - 1, K, V), heads, d)
+    assert np.array_equal(kv, kv2)
+    assert (kv[:, :, :d] < 0).any()
+
+
+def test_constant_v_returns_the_constant_and_hull_bound():
+    rng = np.random.default_rng(11)
+    heads, N, d = 2, 37, 16
+    Q, K = (rng.standard_normal((heads, N, d)) for _ in range(2))
+    cst = rng.standard_normal((heads, 1, d))
+    out = orc.relu_linear_attention(_pack(Q, K, np.broadcast_to(cst, (heads, N, d)).copy()),
+                                    heads, d, 0.0)
+    for h in range(heads):
+        assert np.allclose(out[:, h * d:(h + 1) * d], cst[h], rtol=1e-12, atol=1e-13)
+    V = rng.standard_normal((heads, N, d))
+    out = orc.relu_linear_attention(_pack(Q, K, V), heads, d, 0.0)
+    for h in range(heads):
+        o = out[:, h * d:(h + 1) * d]
+        assert (o <= V[h].max(0) + 1e-12).all() and (o >= V[h].min(0) - 1e-12).all()
+
+
+def test_invariances():
+    rng = np.random.default_rng(21)
+    heads, N, d = 2, 29, 16
+    Q, K, V = (rng.standard_normal((heads, N, d)) for _ in range(3))
+    base = orc.relu_linear_attention(_pack(Q, K, V), heads, d, 0.0)
+    f = lambda q, k, v: orc.relu_linear_attention(_pack(q, k, v), heads, d, 0.0)
+    assert np.allclose(f(2.5 * Q, K, V), base, rtol=1e-12, atol=1e-13)       # no 1/sqrt(d), scale cancels
+    assert np.allclose(f(Q, 0.3 * K, V), base, rtol=1e-12, atol=1e-13)
+    assert np.allclose(f(Q, K, -4.0 * V), -4.0 * base, rtol=1e-12, atol=1e-12)
+    V2 = rng.standard_normal((heads, N, d))
+    assert np.allclose(f(Q, K, V + V2), base + f(Q, K, V2), rtol=1e-11, atol=1e-12)
+    perm = rng.permutation(N)
+    assert np.allclose(f(Q, K[:, perm], V[:, perm]), base, rtol=1e-11, atol=1e-12)
+    # a negative scale is NOT an invariance (ReLU): guards against a missing rectifier
+    assert not np.allclose(f(-Q, K, V), base, atol=1e-3)
+    assert not np.allclose(f(Q, -K, V), base, atol=1e-3)
+
+
+def test_single_token_and_dead_query():
+    d = 16
+    rng = np.random.default_rng(3)
+    Q = np.abs(rng.standard_normal((1, 1, d))); K = np.abs(rng.standard_normal((1, 1, d)))
+    V = rng.standard_normal((1, 1, d))
+    out = orc.relu_linear_attention(_pack(Q, K, V), 1, d, 0.0)
+    assert np.allclose(out, V[0], rtol=1e-13, atol=0)
+    # a query with no positive entry has zero similarity to everything: 0/(0+eps) = 0 exactly
+    N = 9
+    Q = rng.standard_normal((1, N, d)); Q[0, 4] = -np.abs(Q[0, 4]); Q[0, 7] = 0.0
+    K, V = (rng.standard_normal((1, N, d)) for _ in range(2))
+    out = orc.relu_linear_attention(_pack(Q, K, V), 1, d, 1e-15)
+    assert np.array_equal(out[4], np.zeros(d)) and np.array_equal(out[7], np.zeros(d))
+    assert np.isfinite(out).all() and np.abs(out[0]).max() > 0
+
+
+def test_heads_are_independent():
+    rng = np.random.default_rng(8)
+    heads, N, d = 4, 20, 16
+    Q, K, V = (rng.standard_normal((heads, N, d)) for _ in range(3))
+    base = orc.relu_linear_attention(_pack(Q, K, V), heads, d, 1e-15)
+    K2 = K.copy(); K2[2] += 1.0
+    out = orc.relu_linear_attention(_pack(Q, K2, V), heads, d, 1e-15)
+    changed = [not np.array_equal(base[:, h * d:(h + 1) * d], out[:, h * d:(h + 1) * d])
+               for h in range(heads)]
+    assert changed == [False, False, True, False]
+
+
+# ----------------------------------------------------------- depthwise conv
+
+def test_dwconv_box_counts_golden():
+    _, counts = _golden("dwconv_box5_counts_4x6.txt")
+    out = orc.dwconv(np.ones((1, 4, 6, 3)), np.ones((3, 5, 5)))
+    for c in range(3):
+        assert np.array_equal(out[0, :, :, c], counts)
+    # 3x3 on a large map: 9 interior, 6 edges, 4 corners
+    out = orc.dwconv(np.ones((2, 8, 9, 1)), np.ones((1, 3, 3)))[1, :, :, 0]
+    assert out[3, 4] == 9 and out[0, 4] == 6 and out[3, 0] == 6 and out[0, 0] == 4 and out[7, 8] == 4
+    out = orc.dwconv(np.ones((1, 9, 9, 1)), np.ones((1, 5, 5)))[0, :, :, 0]
+    assert out[4, 4] == 25 and out[0, 4] == 15 and out[0, 0] == 9 and out[1, 1] == 16
+
+
+@pytest.mark.parametrize("k", [3, 5, 7])
+def test_dwconv_delta_kernels_pin_orientation(k):
+    rng = np.random.default_rng(k)
+    B, H, W, ch = 2, 6, 7, 4
+    x = rng.standard_normal((B, H, W, ch))
+    p = (k - 1) // 2
+    w = np.zeros((ch, k, k)); w[:, p, p] = 1.0
+    assert np.array_equal(orc.dwconv(x, w), x)
+    # tap (u, v) reads the token at (y+u-p, x+v-p): out = x shifted, zero filled
+    for (u, v) in [(0, 0), (p, k - 1), (k - 1, p - 1), (0, k - 1)]:
+        w = np.zeros((ch, k, k)); w[:, u, v] = 1.0
+        ref = np.zeros_like(x)
+        for y in range(H):
+            for xx in range(W):
+                yy, xs = y + u - p, xx + v - p
+                if 0 <= yy < H and 0 <= xs < W:
+                    ref[:, y, xx] = x[:, yy, xs]
+        assert np.array_equal(orc.dwconv(x, w), ref)
+
+
+@pytest.mark.parametrize("k,H,W", [(5, 9, 11), (3, 2, 2), (5, 3, 4), (5, 1, 1), (7, 5, 6)])
+def test_dwconv_matches_scipy_correlate(k, H, W):
+    rng = np.random.default_rng(100 + k + H)
+    B, ch = 2, 5
+    x = rng.standard_normal((B, H, W, ch)); w = rng.standard_normal((ch, k, k))
+    out = orc.dwconv(x, w)
+    for b in range(B):
+        for c in range(ch):
+            ref = correlate2d(x[b, :, :, c], w[c], mode="same", boundary="fill", fillvalue=0.0)
+            assert np.allclose(out[b, :, :, c], ref, rtol=1e-12, atol=1e-12)
+    # channels do not mix
+    x2 = x.copy(); x2[..., 1] += 1.0
+    out2 = orc.dwconv(x2, w)
+    same = [np.array_equal(out[..., c], out2[..., c]) for c in range(ch)]
+    assert same == [True, False, True, True, True]
+
+
+# ------------------------------------------------------------- grouped 1x1
+
+def test_grouped_pw_is_independent_dxd_blocks():
+    rng = np.random.default_rng(9)
+    heads, d, n = 3, 16, 23
+    ch = 3 * heads * d
+    x = rng.standard_normal((n, ch)); w = rng.standard_normal((ch, d))
+    out = orc.grouped_pw(x, w)
+    G = ch // d
+    ref = np.einsum("nge,goe->ngo", x.reshape(n, G, d), w.reshape(G, d, d)).reshape(n, ch)
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-12)
+    # same thing as a dense block-diagonal 1x1
+    dense = np.zeros((ch, ch))
+    for g in range(G):
+        dense[g * d:(g + 1) * d, g * d:(g + 1) * d] = w[g * d:(g + 1) * d]
+    assert np.allclose(out, x @ dense.T, rtol=1e-12, atol=1e-12)
+    eye = np.tile(np.eye(d), (G, 1))
+    assert np.array_equal(orc.grouped_pw(x, eye), x)
+    # the weight is not transposed: a one-hot row o picks input e of its own group
+    w1 = np.zeros((ch, d)); w1[d + 2, 5] = 1.0
+    o1 = orc.grouped_pw(x, w1)
+    assert np.array_equal(o1[:, d + 2], x[:, d + 5]) and np.count_nonzero(o1.sum(0)) == 1
+
+
+def test_linear_matches_numpy():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((3, 4, 5, 24)); w = rng.standard_normal((40, 24))
+    assert np.allclose(orc.linear(x, w), x @ w.T, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------ whole module
+
+def _recompose(t, heads, d, scales, eps):
+    """The module rebuilt from library routines and the QUADRATIC attention:
+    numpy matmul -> scipy correlate2d -> einsum blocks -> N x N attention -> matmul."""
+    x = t["x"]
+    B, H, W, C = x.shape
+    ch = 3 * heads * d
+    qkv = x @ t["w_qkv"].T
+    maps = [qkv]
+    off = 0
+    for a, k in enumerate(scales):
+        w = t["w_dw"][off:off + ch * k * k].reshape(ch, k, k); off += ch * k * k
+        dw = np.empty_like(qkv)
+        for b in range(B):
+            for c in range(ch):
+                dw[b, :, :, c] = correlate2d(qkv[b, :, :, c], w[c], mode="same")
+        G = ch // d
+        agg = np.einsum("bhwge,goe->bhwgo", dw.reshape(B, H, W, G, d),
+                        t["w_gpw"][a].reshape(G, d, d)).reshape(B, H, W, ch)
+        maps.append(agg)
+    S = len(maps)
+    att = np.empty((B, H * W, S * heads * d))
+    for s, m in enumerate(maps):
+        m = m.reshape(B, H * W, heads, 3, d)
+        for b in range(B):
+            for h in range(heads):
+                Q, K, V = m[b, :, h, 0], m[b, :, h, 1], m[b, :, h, 2]
+                sim = np.maximum(Q, 0) @ np.maximum(K, 0).T
+                o = (sim @ V) / (sim.sum(1, keepdims=True) + eps)
+                att[b, :, (s * heads + h) * d:(s * heads + h + 1) * d] = o
+    out = att @ t["w_proj"].T
+    return qkv, att.reshape(B, H, W, -1), out.reshape(B, H, W, C)
+
+
+@pytest.mark.parametrize("B,C,H,W,heads,d,scales", [
+    (2, 32, 5, 7, 2, 16, (5,)),
+    (1, 48, 6, 4, 3, 16, (3, 5)),
+    (1, 16, 3, 3, 1, 16, ()),
+    (2, 24, 4, 9, 2, 8, (7,)),
+])
+def test_module_matches_brute_force_recomposition(B, C, H, W, heads, d, scales):
+    t = wk.random_module(77 + C, "f32", B, C, H, W, heads, d, scales)
+    qkv, att, out = _recompose(t, heads, d, scales, 1e-15)
+    o_att, o_kv = orc.core_forward(qkv, t["w_dw"], t["w_gpw"], heads, d, scales, 1e-15,
+                                   return_kv=True)
+    assert o_kv.shape == (B, 1 + len(scales), heads, d, d + 1)
+    assert np.allclose(o_att, att, rtol=1e-10, atol=1e-11)
+    o_out = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d,
+                        scales, 1e-15)
+    assert np.allclose(o_out, out, rtol=1e-10, atol=1e-11)
+    # the state of the raw branch, rebuilt directly
+    m = qkv.reshape(B, H * W, heads, 3, d)
+    ref = np.einsum("bnhe,bnhf->bhef", np.maximum(m[:, :, :, 1], 0), m[:, :, :, 2])
+    assert np.allclose(o_kv[:, 0, :, :, :d], ref, rtol=1e-11, atol=1e-11)
+
+
+def test_delta_aggregation_makes_branches_equal():
+    heads, d, k = 2, 16, 5
+    t = wk.random_module(5, "f32", 1, 32, 6, 8, heads, d, (k,))
+    ch = 3 * heads * d
+    w_dw = np.zeros((ch, k, k)); w_dw[:, 2, 2] = 1.0
+    w_gpw = np.tile(np.eye(d), (ch // d, 1))[None]
+    qkv = orc.linear(t["x"], t["w_qkv"])
+    att = orc.core_forward(qkv, w_dw, w_gpw, heads, d, (k,), 1e-15)
+    assert np.allclose(att[..., :heads * d], att[..., heads * d:], rtol=0, atol=1e-14)
+    out = orc.forward(t["x"], t["w_qkv"], w_dw, w_gpw, t["w_proj"], heads, d, (k,), 1e-15)
+    wsum = t["w_proj"][:, :heads * d] + t["w_proj"][:, heads * d:]
+    assert np.allclose(out, att[..., :heads * d] @ wsum.T, rtol=1e-11, atol=1e-12)
+
+
+def test_module_reduces_to_bare_eq3_with_selector_weights():
+    # heads = 1, d = C, no aggregation, w_qkv = three stacked selectors, w_proj = I:
+    # the module is then Eq. (3) on (Q, K, V) = three channel blocks of x.
+    d = 16
+    rng = np.random.default_rng(1)
+    N = 30
+    Q, K, V = (rng.standard_normal((N, d)) for _ in range(3))
+    x = np.concatenate([Q, K, V], axis=1).reshape(1, 5, 6, 3 * d)
+    w_qkv = np.eye(3 * d)
+    out = orc.forward(x, w_qkv, np.zeros(0), np.zeros(0), np.eye(3 * d)[:, :d].copy(),
+                      1, d, (), 1e-15)
+    ref = orc.attention_nxn(Q, K, V, 1e-15)
+    assert np.allclose(out.reshape(N, 3 * d)[:, :d], ref, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(out.reshape(N, 3 * d)[:, d:], np.zeros((N, 2 * d)))
+
+
+def test_batch_images_do_not_mix():
+    heads, d = 2, 16
+    t = wk.random_module(13, "f32", 3, 32, 4, 5, heads, d, (5,))
+    full = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d, (5,), 1e-15)
+    one = orc.forward(t["x"][1:2], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d, (5,), 1e-15)
+    assert np.allclose(full[1:2], one, rtol=1e-13, atol=1e-14)
+
+
+def test_workload_distributions_give_unit_variance_intermediates():
+    # weights ~ N(0, 1/fan_in) keep every intermediate near unit variance; a wrong
+    # fan-in or a mis-strided weight tensor shows up as a variance off by a factor.
+    wl = wk.WORKLOADS[1]
+    t = wk.make_inputs(wl)
+    ch = wl.qkv_channels
+    qkv = orc.linear(t["x"], t["w_qkv"])
+    assert 0.85 < qkv.var() < 1.15
+    dw = orc.dwconv(qkv, t["w_dw"].reshape(ch, 5, 5))
+    assert 0.75 < dw[0, 4:-4, 4:-4].var() < 1.25
+    agg = orc.grouped_pw(dw, t["w_gpw"][0])
+    assert 0.6 < agg[0, 4:-4, 4:-4].var() < 1.4
+    out = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads,
+                      wl.head_dim, wl.scales, wl.eps)
+    assert np.isfinite(out).all() and out.shape == t["x"].shape
+
+
+def test_workload_recipe():
+    for i, wl in wk.WORKLOADS.items():
+        assert wl.seed == 1000 + i and wl.heads * wl.head_dim == wl.C and wl.head_dim == 16
+    t5 = wk.make_inputs(wk.WORKLOADS[5], batch=1)
+    frac = (t5["x"] == 0).mean()
+    assert 0.09 < frac < 0.11
+    assert np.array_equal(t5["x"], t5["x"].astype(np.float16).astype(np.float64))
+    t4 = wk.make_inputs(wk.WORKLOADS[4], batch=1)
+    assert t4["w_dw"].size == 384 * (9 + 25) and t4["w_gpw"].shape == (2, 384, 16)
+    import torch
+    xb = torch.from_numpy(t4["w_proj"]).to(torch.bfloat16).double().numpy()
+    assert np.array_equal(xb, t4["w_proj"])            # already bf16-representable
+    assert wk.WORKLOADS[5].algorithmic_bytes() == 369098752
+    assert wk.WORKLOADS[4].algorithmic_bytes() == 218103808
+    assert wk.WORKLOADS[5].algorithmic_bytes(core_only=True) == 268435456
