@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the MSLA hot path on one MI355X.
+
+A "step" is one pass of the whole module (Q/K/V projection, multi-scale
+aggregation + Eq. (3) state, fused normalise-and-apply + output projection)
+over one batch of synthetic input that is already resident in HBM.
+
+Prints ONE JSON line: whole-job tokens/s on the headline workload (8 x 256 x
+64 x 128 tokens, fp16, scales {raw, 5x5}, 10 % zeros), the roofline of the
+dominant kernel measured live with HIP events on the launch stream, and the
+fp64 CPU oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
+
+STAGES = ("qkv_project", "aggregate_state", "state_finalize", "apply_project")
+
+
+def _hip():
+    for name in ("libamdhip64.so", "/opt/rocm/lib/libamdhip64.so"):
+        try:
+            return ctypes.CDLL(name)
+        except OSError:
+            continue
+    raise RuntimeError("libamdhip64.so not found")
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime (timing enabled)."""
+
+    def __init__(self, n: int):
+        self.hip = _hip()
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = []
+        for _ in range(n):
+            h = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(h))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.handles.append(h.value)
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def sync(self, i: int):
+        self.hip.hipEventSynchronize(self.handles[i])
+
+    def destroy(self):
+        for h in self.handles:
+            self.hip.hipEventDestroy(h)
+        self.handles = []
+
+
+def stage_algorithmic_bytes(wl) -> dict:
+    """Algorithmic HBM bytes per launch of each stage, in units of e*Ct*T
+    (x and out have C = Ct channels in every workload): the projection reads x
+    and writes Q, K, V (4); the aggregation pass reads Q, K, V and writes the A
+    aggregated Q maps (3 + A); the apply pass reads the S = 1 + A Q maps and
+    writes out (2 + A).  Their sum is the module's e*C*T*(9 + 2A)."""
+    A = len(wl.scales)
+    unit = wl.elem_bytes * wl.heads * wl.head_dim * wl.tokens
+    return {"qkv_project": 4 * unit, "aggregate_state": (3 + A) * unit, "state_finalize": 0,
+            "apply_project": (2 + A) * unit}
+
+
+def read_traffic(path: str, kernel: str):
+    """Optional measured HBM traffic (bytes per launch) from a rocprofv3 --pmc summary:
+    a line 'TRAFFIC_BYTES_PER_LAUNCH <stage> <bytes>'."""
+    try:
+        with open(path) as f:
+            for line in f:
+                m = re.match(r"TRAFFIC_BYTES_PER_LAUNCH\s+(\S+)\s+([0-9.eE+]+)", line.strip())
+                if m and m.group(1) == kernel:
+                    return float(m.group(2))
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=5, help="index into workloads.WORKLOADS (5 = headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_cfg5.txt"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the module is a single-device kernel path; "
+                 "see DESIGN.md for how it would shard). Run with --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2205_14756_amd import msla
+    from paper_2205_14756_amd import workloads as wk
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    msla.load_library()            # fails loudly if the HIP library is missing
+    wl = wk.WORKLOADS[args.workload]
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype]
+    t = wk.make_inputs(wl)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(tdt).cuda().contiguous()
+    x, w_qkv, w_proj = dev(t["x"]), dev(t["w_qkv"]), dev(t["w_proj"])
+    w_dw = dev(t["w_dw"]) if wl.scales else None
+    w_gpw = dev(t["w_gpw"]) if wl.scales else None
+    out = torch.empty_like(x)
+    ws = msla.new_workspace(wl.B, wl.C, wl.H, wl.W, wl.heads, wl.head_dim, wl.scales, tdt)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        msla.msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, wl.heads, wl.head_dim, wl.scales, wl.eps,
+                          out=out, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = wl.tokens * args.steps / elapsed
+
+    # ---- per-stage durations: the same K steps again, with HIP events recorded on the launch
+    # stream between the stages (kept out of the loop above so they cannot perturb `value`)
+    ev = HipEvents(5 * args.steps)
+    for i in range(args.steps):
+        msla.msla_forward_profiled(x, w_qkv, w_dw, w_gpw, w_proj, wl.heads, wl.head_dim, wl.scales, wl.eps,
+                                   out, ws, ev.handles[5 * i:5 * i + 5], stream=stream)
+    torch.cuda.synchronize()
+    stage_ms = {s: 0.0 for s in STAGES}
+    for i in range(args.steps):
+        for j, s in enumerate(STAGES):
+            stage_ms[s] += ev.elapsed_ms(5 * i + j, 5 * i + j + 1)
+    ev.destroy()
+    stage_ms = {s: v / args.steps for s, v in stage_ms.items()}
+    alg = stage_algorithmic_bytes(wl)
+    dominant = max(STAGES, key=lambda s: stage_ms[s])
+    achieved = alg[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(args.traffic_file, dominant),
+                "algorithmic_bytes": alg[dominant], "avg_ms": round(stage_ms[dominant], 5),
+                "stage_ms": {s: round(v, 5) for s, v in stage_ms.items()},
+                "module_algorithmic_bytes": wl.algorithmic_bytes(),
+                "module_frac": round(wl.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- the fp64 CPU oracle as it stands, on the host cores (reported baseline + parity check)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import msla_oracle as orc
+        t1 = time.perf_counter()
+        ref = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads, wl.head_dim,
+                          wl.scales, wl.eps)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": round(wl.tokens / cpu_s, 1), "unit": "tokens/s", "cores": orc.num_threads(),
+               "kind": "oracle", "sample": f"the full {wl.name} batch ({wl.tokens} tokens), one pass, "
+                                            f"{cpu_s:.2f} s wall"}
+        got = out.to(torch.float64).cpu().numpy()
+        parity = float(np.abs(got - ref).max() / np.abs(ref).max())
+
+    line = {
+        "metric": "MSLA module tokens/s (64x128 tokens, C=256, fp16)", "value": round(tokens_per_s, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "C": wl.C, "H": wl.H, "W": wl.W, "heads": wl.heads,
+                   "head_dim": wl.head_dim, "scales": ["raw"] + [f"{k}x{k}" for k in wl.scales],
+                   "tokens": wl.tokens, "zero_frac": wl.zero_frac},
+        "roofline": roofline, "cpu_baseline": cpu, "max_err_over_max_out": parity,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

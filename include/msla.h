@@ -1,0 +1,135 @@
+/*
+ * msla.h -- C ABI of the MI355X (gfx950) multi-scale linear attention library.
+ *
+ * The library computes the multi-scale linear attention (MSLA) module of
+ * EfficientViT (paper Section 3.1, Fig. 2 right):
+ *
+ *   x --1x1 projection--> Q/K/V token maps                     (Section 3.1, Eq. (1): Q = x W_Q ...)
+ *     --per aggregated scale: depthwise k x k conv + grouped 1x1 conv
+ *       (3*heads groups of d channels) --> multi-scale Q/K/V    (Section 3.1, last paragraph)
+ *     --per branch, per head: ReLU linear attention             (Eqs. (2), (3))
+ *         KV   = sum_n relu(K_n)^T [V_n, 1]            (d x (d+1), once per image/branch/head)
+ *         att_n = relu(Q_n) KV[:, :d] / (relu(Q_n) KV[:, d] + eps)
+ *     --concatenate branches and heads, 1x1 projection--> out   (Section 3.1, last sentence)
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers (HBM), 16-byte aligned, row-major,
+ *     in the storage dtype `dt`; every sum is accumulated in fp32.  `scales`
+ *     is a HOST pointer.  `stream` is a hipStream_t passed as void*.
+ *   - The caller owns every buffer, including `workspace` (size it with
+ *     msla_workspace_bytes).  The library allocates and frees nothing, keeps
+ *     no state between calls and is re-entrant as long as concurrent calls
+ *     use different workspaces and outputs.
+ *   - Work is enqueued on `stream`; the call returns without synchronising.
+ *     Buffers must stay alive and unmodified until the stream has passed it.
+ *     Outputs must not alias inputs or the workspace.
+ *   - All validation happens on the host before the first launch: a call that
+ *     returns MSLA_ERR_INVALID_ARG, _UNSUPPORTED or _WORKSPACE has enqueued
+ *     nothing.  No exception, abort or exit crosses this boundary.
+ *
+ * Shapes.  T = B*H*W tokens, Ct = heads*head_dim, A = n_scales aggregated
+ * scales, S = 1 + A branches (branch 0 is the raw Q/K/V map and is always
+ * present; branch a+1 is aggregated with a scales[a] x scales[a] kernel; every
+ * aggregated branch reads the raw map).
+ *   x      [B, H, W, C]            (MSLA_NHWC: a token is one row of C channels)
+ *   w_qkv  [3*Ct, C]               row o = (h*3 + t)*head_dim + e, t = 0:Q 1:K 2:V,
+ *                                  so each (head, Q/K/V) pair is one contiguous group
+ *                                  of head_dim channels (the 3*heads groups of Section 3.1)
+ *   qkv    [B, H, W, 3*Ct]         same channel order as the rows of w_qkv
+ *   w_dw   concat over a of [3*Ct, k_a, k_a]   depthwise filters; stride 1, zero padding
+ *                                  (k_a-1)/2, cross-correlation (tap (u,v) reads token
+ *                                  (y+u-p, x+v-p))
+ *   w_gpw  [A, 3*Ct, head_dim]     grouped 1x1: out channel o, input e of o's own group
+ *   w_proj [C, S*Ct]               column m = (s*heads + h)*head_dim + f
+ *   att    [B, H, W, S*Ct]         column order as w_proj's columns
+ *   out    [B, H, W, C]
+ * No bias, normalisation or activation other than the ReLUs of Eq. (2).
+ *
+ * Supported: head_dim == 16; scales[a] in {3, 5}; n_scales <= 7;
+ * C and Ct multiples of 16; MSLA_NHWC.  Anything else that is otherwise
+ * well-formed returns MSLA_ERR_UNSUPPORTED.
+ */
+#ifndef MSLA_H_
+#define MSLA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MSLA_OK = 0,
+    MSLA_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, even kernel size, eps < 0, bad enum, misaligned pointer */
+    MSLA_ERR_UNSUPPORTED = -2,  /* well-formed but outside what the kernels cover (see above) */
+    MSLA_ERR_WORKSPACE = -3,    /* workspace_bytes smaller than msla_workspace_bytes reports */
+    MSLA_ERR_LAUNCH = -4        /* the HIP runtime reported an error while enqueueing */
+} msla_status;
+
+typedef enum { MSLA_F32 = 0, MSLA_F16 = 1, MSLA_BF16 = 2 } msla_dtype;   /* storage type; sums are fp32 */
+typedef enum { MSLA_NHWC = 0, MSLA_NCHW = 1 } msla_layout;               /* of x and out */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* msla_error_string(msla_status status);
+
+/* Bytes of device workspace that any of the calls below needs for this shape
+ * (the largest over the entry points).  *bytes is written only on MSLA_OK. */
+msla_status msla_workspace_bytes(int B, int C, int H, int W, int heads, int head_dim,
+                                 const int* scales, int n_scales, msla_dtype dt,
+                                 size_t* bytes);
+
+/* The whole module (Section 3.1, Fig. 2 right): out = MSLA(x).
+ * eps is added to the denominator of Eq. (3) in fp32 (the equation has none;
+ * a token whose rectified query is all zero then yields exactly 0). */
+msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw,
+                         const void* w_gpw, const void* w_proj, void* out,
+                         void* workspace, size_t workspace_bytes,
+                         int B, int C, int H, int W, int heads, int head_dim,
+                         const int* scales, int n_scales,
+                         float eps, msla_dtype dt, msla_layout layout, void* stream);
+
+/* msla_forward with stage timing (for benchmarks; same computation, Section 3.1).
+ * events: HOST array of 5 hipEvent_t created by the caller with timing enabled.  They are
+ * recorded on `stream`: [0] before the first kernel, [1] after the Q/K/V projection,
+ * [2] after the aggregation kernels (partial states written), [3] after the state
+ * finalize kernel, [4] after the fused apply + output projection. */
+msla_status msla_forward_profiled(const void* x, const void* w_qkv, const void* w_dw,
+                                  const void* w_gpw, const void* w_proj, void* out,
+                                  void* workspace, size_t workspace_bytes,
+                                  int B, int C, int H, int W, int heads, int head_dim,
+                                  const int* scales, int n_scales,
+                                  float eps, msla_dtype dt, msla_layout layout, void* stream,
+                                  void* const* events);
+
+/* The module without its two projections: multi-scale token aggregation and
+ * per-head ReLU linear attention on a given projected map (Section 3.1,
+ * Eqs. (2)-(3)): att = concat_s LinearAttention(branch_s(qkv)). */
+msla_status msla_core_forward(const void* qkv, const void* w_dw, const void* w_gpw,
+                              void* att, void* workspace, size_t workspace_bytes,
+                              int B, int H, int W, int heads, int head_dim,
+                              const int* scales, int n_scales,
+                              float eps, msla_dtype dt, void* stream);
+
+/* Stage: multi-scale aggregation and the once-per-image state of Eq. (3).
+ *   q_ms [B, H, W, S*Ct] (storage dtype): the Q tokens of every branch, column
+ *        (s*heads + h)*head_dim + e  (branch 0 = the raw Q; may be NULL)
+ *   kv   [B, S, heads, head_dim, head_dim+1] fp32:
+ *        kv[..., e, f] = sum_n relu(K_n[e]) V_n[f],  kv[..., e, head_dim] = sum_n relu(K_n[e]),
+ *        the sum running over the H*W tokens of one image and one branch. */
+msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void* w_gpw,
+                                  void* q_ms, float* kv,
+                                  void* workspace, size_t workspace_bytes,
+                                  int B, int H, int W, int heads, int head_dim,
+                                  const int* scales, int n_scales,
+                                  msla_dtype dt, void* stream);
+
+/* Stage: a 1x1 projection of a token map (Section 3.1: Q = x W_Q etc., and the
+ * final projection):  y[n, o] = sum_c x[n, c] * w[o, c],
+ *   x [n_tokens, c_in], w [c_out, c_in], y [n_tokens, c_out]; c_in, c_out multiples of 16. */
+msla_status msla_linear(const void* x, const void* w, void* y,
+                        long n_tokens, int c_in, int c_out, msla_dtype dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSLA_H_ */

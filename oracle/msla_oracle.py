@@ -198,3 +198,101 @@ def forward(x, w_qkv, w_dw, w_gpw, w_proj, heads: int, d: int, scales, eps: floa
     if rc != 0:
         raise MemoryError("msla_oracle_forward: out of memory")
     return out
+
+
+# ----------------------------------------------------------------------------
+# The same module composed stage by stage (Fig. 2 right), with two hooks that
+# the parity tests need and the one-call C entry points above do not have:
+#
+#   store   callable(ndarray) -> ndarray or None.  Reading "16-bit storage,
+#           fp32 sums": a token map that a two-pass evaluation of Eq. (3) has
+#           to keep between its passes is STORED, i.e. rounded once to the
+#           storage type: the projected Q/K/V tokens, and the aggregated Q
+#           tokens of every branch (aggregated K and V only feed the sums of
+#           Eq. (3) and need not be kept).  `store` is that rounding (the
+#           caller passes the input generator's rounding; this file does no
+#           rounding of its own).  None = nothing is rounded (plain fp64).
+#   q_tokens  optional [B,H,W,S*heads*d] array that replaces the Q tokens of
+#           every branch in Eq. (3).  Eq. (3) is 0/0 where a token's rectified
+#           query vanishes and discontinuous next to it: which components of Q
+#           pass the ReLU is a discrete decision taken by floating point, so a
+#           comparison has to take it on the same stored values on both sides.
+# ----------------------------------------------------------------------------
+
+def branch_maps(qkv, w_dw, w_gpw, heads: int, d: int, scales, store=None):
+    """[raw map, aggregated map per scale], each [B,H,W,3*heads*d]; every
+    aggregated branch reads the raw map (Section 3.1, last paragraph)."""
+    qkv = _f64(qkv)
+    ch = 3 * heads * d
+    w_dw = _f64(w_dw).reshape(-1)
+    maps = [qkv]
+    off = 0
+    for a, k in enumerate(scales):
+        w = w_dw[off:off + ch * k * k].reshape(ch, k, k)
+        off += ch * k * k
+        agg = grouped_pw(dwconv(qkv, w), _f64(w_gpw)[a])
+        if store is not None:
+            B, H, W, _ = agg.shape
+            v = agg.reshape(B, H, W, heads, 3, d)
+            v[..., 0, :] = _f64(store(np.ascontiguousarray(v[..., 0, :])))
+        maps.append(agg)
+    return maps
+
+
+def q_tokens_of(maps, heads: int, d: int) -> np.ndarray:
+    """The Q tokens of every branch, [B,H,W,S*heads*d], column (s*heads+h)*d+e."""
+    B, H, W, _ = maps[0].shape
+    return np.concatenate([m.reshape(B, H, W, heads, 3, d)[..., 0, :].reshape(B, H, W, heads * d)
+                           for m in maps], axis=-1)
+
+
+def attention_of_maps(maps, heads: int, d: int, eps: float, q_tokens=None):
+    """Eq. (3) per image / branch / head on the given branch maps.
+    Returns (att [B,H,W,S*heads*d], kv [B,S,heads,d,d+1])."""
+    B, H, W, ch = maps[0].shape
+    S = len(maps)
+    N = H * W
+    Ct = heads * d
+    att = np.empty((B, N, S * Ct), dtype=np.float64)
+    kv = np.empty((B, S, heads, d, d + 1), dtype=np.float64)
+    for s, m in enumerate(maps):
+        m = _f64(m).reshape(B, N, ch)
+        if q_tokens is not None:
+            m = m.copy().reshape(B, N, heads, 3, d)
+            m[:, :, :, 0, :] = _f64(q_tokens).reshape(B, N, S, heads, d)[:, :, s]
+            m = m.reshape(B, N, ch)
+        for b in range(B):
+            tok = np.ascontiguousarray(m[b])
+            kv[b, s] = kv_state(tok, heads, d)
+            att[b, :, s * Ct:(s + 1) * Ct] = apply(tok, kv[b, s], eps)
+    return att.reshape(B, H, W, S * Ct), kv
+
+
+def gate_margin(q_tokens, kv, heads: int, d: int) -> np.ndarray:
+    """Conditioning of Eq. (3) per (token, head-branch):
+    (relu(Q).Ksum) / (|Q|.Ksum) in [0, 1]; small values mean the denominator is
+    a small remainder of cancelled rounding errors of Q.  [B,H,W,S*heads]."""
+    q = _f64(q_tokens)
+    B, H, W, _ = q.shape
+    S = kv.shape[1]
+    q = q.reshape(B, H * W, S, heads, d)
+    ks = _f64(kv)[..., d]                                  # [B,S,heads,d]
+    num = np.einsum("bnshe,bshe->bnsh", np.maximum(q, 0.0), ks)
+    den = np.einsum("bnshe,bshe->bnsh", np.abs(q), ks)
+    out = np.where(den > 0, num / np.where(den > 0, den, 1.0), 1.0)
+    return out.reshape(B, H, W, S * heads)
+
+
+def forward_staged(x, w_qkv, w_dw, w_gpw, w_proj, heads: int, d: int, scales, eps: float,
+                   store=None, q_tokens=None, return_parts: bool = False):
+    """Whole module, stage by stage.  With store=None and q_tokens=None this is
+    exactly `forward` (pinned by a test)."""
+    qkv = linear(x, w_qkv)
+    if store is not None:
+        qkv = _f64(store(qkv))
+    maps = branch_maps(qkv, w_dw, w_gpw, heads, d, scales, store)
+    att, kv = attention_of_maps(maps, heads, d, eps, q_tokens)
+    out = linear(att, w_proj)
+    if return_parts:
+        return out, {"qkv": qkv, "maps": maps, "att": att, "kv": kv, "q_tokens": q_tokens_of(maps, heads, d)}
+    return out

@@ -1,0 +1,290 @@
+// Host side of the C ABI declared in include/msla.h: argument validation,
+// workspace carving and the launch sequence.  No allocation, no global state,
+// no synchronisation; every failure before the first launch leaves the stream
+// untouched.
+#include "../../include/msla.h"
+
+#include <stdint.h>
+
+#include "msla_kernels.h"
+
+namespace {
+
+constexpr int kMaxScales = 7;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+size_t elem_size(msla_dtype dt) { return dt == MSLA_F32 ? 4 : 2; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Shape {
+    int B, H, W, heads, S;
+    long N, T;
+    int Ct;
+    int n_scales;
+    int scales[kMaxScales];
+    // state reduction split
+    int nchunks, tiles_per_chunk;
+};
+
+// Checks everything about the shape that does not involve pointers.
+msla_status check_shape(int B, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
+                        int dt, Shape* s) {
+    if (B <= 0 || H <= 0 || W <= 0 || heads <= 0 || head_dim <= 0 || n_scales < 0) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > 0 && scales == nullptr) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    for (int i = 0; i < n_scales; ++i)
+        if (scales[i] < 1 || scales[i] % 2 == 0) return MSLA_ERR_INVALID_ARG;
+    if (head_dim != 16) return MSLA_ERR_UNSUPPORTED;
+    if (n_scales > kMaxScales) return MSLA_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_scales; ++i)
+        if (scales[i] != 3 && scales[i] != 5) return MSLA_ERR_UNSUPPORTED;
+    const long N = (long)H * W;
+    const long T = N * B;
+    if (N > (1L << 30) || T > (1L << 31) || (long)heads * 16 > (1L << 20)) return MSLA_ERR_UNSUPPORTED;
+    s->B = B; s->H = H; s->W = W; s->heads = heads; s->S = 1 + n_scales;
+    s->N = N; s->T = T; s->Ct = heads * 16; s->n_scales = n_scales;
+    for (int i = 0; i < n_scales; ++i) s->scales[i] = scales[i];
+    // Split each (image, head) over enough workgroups to fill the chip; every
+    // workgroup then emits one partial state.  A "tile" is 8x32 tokens for the
+    // aggregating kernel, 64 consecutive tokens when there is no aggregated scale.
+    long tiles;
+    if (n_scales > 0)
+        tiles = (long)((H + msla::kAggTileH - 1) / msla::kAggTileH) * ((W + msla::kAggTileW - 1) / msla::kAggTileW);
+    else
+        tiles = (N + 63) / 64;
+    const long target_blocks = 1024;
+    long want = (target_blocks + (long)B * heads - 1) / ((long)B * heads);
+    if (want < 1) want = 1;
+    if (want > tiles) want = tiles;
+    const long tpc = (tiles + want - 1) / want;
+    s->tiles_per_chunk = (int)tpc;
+    s->nchunks = (int)((tiles + tpc - 1) / tpc);
+    return MSLA_OK;
+}
+
+struct Workspace {
+    size_t q_ms, kv_raw, partials, kv32, kvfrag, kvscale, total;
+};
+
+Workspace carve(const Shape& s, msla_dtype dt) {
+    const size_t e = elem_size(dt);
+    const size_t n_states = (size_t)s.B * s.S * s.heads;
+    Workspace w;
+    size_t off = 0;
+    w.q_ms = off;     off += align_up((size_t)s.T * s.S * s.Ct * e);
+    w.kv_raw = off;   off += align_up((size_t)s.T * 2 * s.Ct * e);
+    w.partials = off; off += align_up(n_states * s.nchunks * 272 * sizeof(float));
+    w.kv32 = off;     off += align_up(n_states * 272 * sizeof(float));
+    w.kvfrag = off;   off += align_up(n_states * 2048);
+    w.kvscale = off;  off += align_up(n_states * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+size_t dw_weight_elems(const Shape& s, int upto) {
+    size_t n = 0;
+    for (int i = 0; i < upto; ++i) n += (size_t)3 * s.Ct * s.scales[i] * s.scales[i];
+    return n;
+}
+
+// Aggregation + state for all branches.  The raw maps are given as three strided views.
+msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, int q_hs, const void* k,
+                      long k_ts, int k_hs, const void* v, long v_ts, int v_hs, const void* w_dw,
+                      const void* w_gpw, char* ws, const Workspace& wo, void* q_ms, int copy_raw_q,
+                      hipStream_t stream, void* event_before_finalize = nullptr) {
+    const size_t e = elem_size(dt);
+    msla::AggregateArgs a;
+    a.q = q; a.k = k; a.v = v;
+    a.q_ts = q_ts; a.k_ts = k_ts; a.v_ts = v_ts;
+    a.q_hs = q_hs; a.k_hs = k_hs; a.v_hs = v_hs;
+    a.q_ms = q_ms;
+    a.partials = reinterpret_cast<float*>(ws + wo.partials);
+    a.B = s.B; a.H = s.H; a.W = s.W; a.heads = s.heads; a.S = s.S;
+    a.nchunks = s.nchunks; a.tiles_per_chunk = s.tiles_per_chunk;
+    if (s.n_scales == 0) {
+        a.w_dw = nullptr; a.w_gpw = nullptr; a.ks = 0; a.branch = 0; a.do_raw = 1; a.copy_raw_q = copy_raw_q;
+        if (msla::launch_raw_state((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
+    }
+    for (int i = 0; i < s.n_scales; ++i) {
+        a.w_dw = static_cast<const char*>(w_dw) + dw_weight_elems(s, i) * e;
+        a.w_gpw = static_cast<const char*>(w_gpw) + (size_t)i * 3 * s.Ct * 16 * e;
+        a.ks = s.scales[i];
+        a.branch = i + 1;
+        a.do_raw = (i == 0);
+        a.copy_raw_q = (i == 0) ? copy_raw_q : 0;
+        if (msla::launch_aggregate((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
+    }
+    if (event_before_finalize &&
+        hipEventRecord(static_cast<hipEvent_t>(event_before_finalize), stream) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    const int n_states = s.B * s.S * s.heads;
+    if (msla::launch_state_finalize((int)dt, a.partials, reinterpret_cast<float*>(ws + wo.kv32), ws + wo.kvfrag,
+                                    reinterpret_cast<float*>(ws + wo.kvscale), n_states, s.nchunks,
+                                    stream) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* msla_error_string(msla_status status) {
+    switch (status) {
+        case MSLA_OK: return "MSLA_OK";
+        case MSLA_ERR_INVALID_ARG: return "MSLA_ERR_INVALID_ARG: null/misaligned pointer, non-positive size, even kernel size, negative eps or unknown enum";
+        case MSLA_ERR_UNSUPPORTED: return "MSLA_ERR_UNSUPPORTED: shape, head size, kernel size or layout not covered by the kernels";
+        case MSLA_ERR_WORKSPACE: return "MSLA_ERR_WORKSPACE: workspace smaller than msla_workspace_bytes reports";
+        case MSLA_ERR_LAUNCH: return "MSLA_ERR_LAUNCH: HIP error while enqueueing";
+    }
+    return "unknown msla_status";
+}
+
+msla_status msla_workspace_bytes(int B, int C, int H, int W, int heads, int head_dim, const int* scales,
+                                 int n_scales, msla_dtype dt, size_t* bytes) {
+    if (bytes == nullptr || C <= 0) return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    const msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    if (C % 16 != 0) return MSLA_ERR_UNSUPPORTED;
+    *bytes = carve(s, dt).total;
+    return MSLA_OK;
+}
+
+static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                                const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B,
+                                int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
+                                float eps, msla_dtype dt, msla_layout layout, void* stream,
+                                void* const* events) {
+    if (!x || !w_qkv || !w_proj || !out || !workspace || C <= 0) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
+    if (layout != MSLA_NHWC && layout != MSLA_NCHW) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
+        !aligned16(w_dw) || !aligned16(w_gpw))
+        return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    if (C % 16 != 0 || layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
+    const Workspace wo = carve(s, dt);
+    if (workspace_bytes < wo.total) return MSLA_ERR_WORKSPACE;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const size_t e = elem_size(dt);
+    void* q_ms = ws + wo.q_ms;
+    char* kv_raw = ws + wo.kv_raw;
+    const long q_ms_ts = (long)s.S * s.Ct;
+
+    auto mark = [&](int i) -> bool {
+        return events == nullptr || hipEventRecord(static_cast<hipEvent_t>(events[i]), hs) == hipSuccess;
+    };
+    if (!mark(0)) return MSLA_ERR_LAUNCH;
+    // Q/K/V projection; raw Q lands in the branch-0 columns of the multi-scale Q map
+    if (msla::launch_qkv_project((int)dt, x, w_qkv, q_ms, q_ms_ts, kv_raw, s.T, C, s.heads, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    if (!mark(1)) return MSLA_ERR_LAUNCH;
+    // aggregation + Eq. (3) state
+    st = run_state(s, dt, q_ms, q_ms_ts, 16, kv_raw, 2L * s.Ct, 32, kv_raw + 16 * e, 2L * s.Ct, 32, w_dw, w_gpw,
+                   ws, wo, q_ms, /*copy_raw_q=*/0, hs, events ? events[2] : nullptr);
+    if (st != MSLA_OK) return st;
+    if (!mark(3)) return MSLA_ERR_LAUNCH;
+    // normalise-and-apply fused with the output projection
+    if (msla::launch_apply_project((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale),
+                                   w_proj, out, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    if (!mark(4)) return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                         const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B, int C,
+                         int H, int W, int heads, int head_dim, const int* scales, int n_scales, float eps,
+                         msla_dtype dt, msla_layout layout, void* stream) {
+    return forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads,
+                        head_dim, scales, n_scales, eps, dt, layout, stream, nullptr);
+}
+
+msla_status msla_forward_profiled(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                                  const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B,
+                                  int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
+                                  float eps, msla_dtype dt, msla_layout layout, void* stream,
+                                  void* const* events) {
+    if (events == nullptr) return MSLA_ERR_INVALID_ARG;
+    for (int i = 0; i < 5; ++i)
+        if (events[i] == nullptr) return MSLA_ERR_INVALID_ARG;
+    return forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads,
+                        head_dim, scales, n_scales, eps, dt, layout, stream, events);
+}
+
+msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms_out,
+                                  float* kv, void* workspace, size_t workspace_bytes, int B, int H, int W,
+                                  int heads, int head_dim, const int* scales, int n_scales, msla_dtype dt,
+                                  void* stream) {
+    if (!qkv || !workspace || !kv) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(qkv) || !aligned16(workspace) || !aligned16(w_dw) || !aligned16(w_gpw) ||
+        !aligned16(q_ms_out) || !aligned16(kv))
+        return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    const Workspace wo = carve(s, dt);
+    if (workspace_bytes < wo.total) return MSLA_ERR_WORKSPACE;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const size_t e = elem_size(dt);
+    const char* base = static_cast<const char*>(qkv);
+    void* q_ms = q_ms_out ? q_ms_out : static_cast<void*>(ws + wo.q_ms);
+    st = run_state(s, dt, base, 3L * s.Ct, 48, base + 16 * e, 3L * s.Ct, 48, base + 32 * e, 3L * s.Ct, 48, w_dw,
+                   w_gpw, ws, wo, q_ms, /*copy_raw_q=*/1, hs);
+    if (st != MSLA_OK) return st;
+    const size_t n_states = (size_t)s.B * s.S * s.heads;
+    if (hipMemcpyAsync(kv, ws + wo.kv32, n_states * 272 * sizeof(float), hipMemcpyDeviceToDevice, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+msla_status msla_core_forward(const void* qkv, const void* w_dw, const void* w_gpw, void* att, void* workspace,
+                              size_t workspace_bytes, int B, int H, int W, int heads, int head_dim,
+                              const int* scales, int n_scales, float eps, msla_dtype dt, void* stream) {
+    if (!qkv || !att || !workspace) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(qkv) || !aligned16(att) || !aligned16(workspace) || !aligned16(w_dw) || !aligned16(w_gpw))
+        return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    const Workspace wo = carve(s, dt);
+    if (workspace_bytes < wo.total) return MSLA_ERR_WORKSPACE;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const size_t e = elem_size(dt);
+    const char* base = static_cast<const char*>(qkv);
+    void* q_ms = ws + wo.q_ms;
+    st = run_state(s, dt, base, 3L * s.Ct, 48, base + 16 * e, 3L * s.Ct, 48, base + 32 * e, 3L * s.Ct, 48, w_dw,
+                   w_gpw, ws, wo, q_ms, /*copy_raw_q=*/1, hs);
+    if (st != MSLA_OK) return st;
+    if (msla::launch_apply((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale), att, s.T,
+                           (int)s.N, s.S * s.heads, eps, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+msla_status msla_linear(const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out,
+                        msla_dtype dt, void* stream) {
+    if (!x || !w || !y || n_tokens <= 0 || c_in <= 0 || c_out <= 0) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MSLA_ERR_INVALID_ARG;
+    if (c_in % 16 != 0 || c_out % 16 != 0 || n_tokens > (1L << 31)) return MSLA_ERR_UNSUPPORTED;
+    if (msla::launch_linear((int)dt, x, w, y, n_tokens, c_in, c_out, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,178 @@
+// Device-side building blocks shared by the gfx950 kernels: storage-type traits,
+// 8/16-byte vector moves, and the MFMA fragment conventions used everywhere.
+//
+// Fragment convention (all 16x16 MFMAs, wave64).  Lane l is (x, q) with
+// x = l % 16 and q = l / 16.
+//   "row operand"  A (16 x K):  lane (x, q) holds A[x][K-slots owned by q]
+//   "col operand"  B (K x 16):  lane (x, q) holds B[K-slots owned by q][x]
+//   result         D (16 x 16): lane (x, q) holds D[4q + r][x], r = 0..3
+// A contraction index only has to be paired consistently between A and B, so
+// for a 16-wide contraction the lane (x, q) always owns indices 4q..4q+3
+// ("Frag"), whatever instruction the storage type maps to.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace msla {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHeadDim = 16;            // d of Section 3.1; the only head size built
+constexpr int kStateSize = 16 * 17;     // d x (d+1) floats of the Eq. (3) state
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+template <class T> struct Traits;
+
+// ---------------------------------------------------------------- fp16
+template <> struct Traits<_Float16> {
+    typedef _Float16 elem;
+    typedef f16x4 Frag;                 // 4 contraction slots
+    typedef f16x8 Vec;                  // 16 bytes = 8 contraction slots
+    static constexpr int kVec = 8;
+    static constexpr bool kSplit = true;    // state fragments carry a hi and a lo half
+    static constexpr bool kHiLo = false;    // 11 significant bits: in-register operands are rounded once
+    static __device__ __forceinline__ float to_f32(elem v) { return (float)v; }
+    static __device__ __forceinline__ elem from_f32(float v) { return (elem)v; }
+    static __device__ __forceinline__ f32x4 mma16(f32x4 c, Frag a, Frag b) {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4 mma_vec(f32x4 c, Vec a, Vec b) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------- bf16
+template <> struct Traits<__bf16> {
+    typedef __bf16 elem;
+    typedef bf16x4 Frag;
+    typedef bf16x8 Vec;
+    static constexpr int kVec = 8;
+    static constexpr bool kSplit = true;
+    // 8 significant bits are too few for operands that only live in registers or LDS (depthwise
+    // sums, aggregated K/V, attention rows): those are fed to the matrix cores as hi + lo pairs.
+    static constexpr bool kHiLo = true;
+    static __device__ __forceinline__ float to_f32(elem v) { return (float)v; }
+    static __device__ __forceinline__ elem from_f32(float v) { return (elem)v; }
+    static __device__ __forceinline__ f32x4 mma16(f32x4 c, Frag a, Frag b) {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, a),
+                                                         __builtin_bit_cast(i16x4, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4 mma_vec(f32x4 c, Vec a, Vec b) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------- fp32
+// True fp32 matrix instruction (16x16x4), four per 16-wide contraction.  The
+// hardware contracts over q in each step; step r pairs a[r] with b[r], i.e.
+// contraction index 4q + r, which is exactly the Frag convention.
+template <> struct Traits<float> {
+    typedef float elem;
+    typedef f32x4 Frag;
+    typedef f32x4 Vec;                  // 16 bytes = 4 contraction slots
+    static constexpr int kVec = 4;
+    static constexpr bool kSplit = false;
+    static constexpr bool kHiLo = false;
+    static __device__ __forceinline__ float to_f32(elem v) { return v; }
+    static __device__ __forceinline__ elem from_f32(float v) { return v; }
+    static __device__ __forceinline__ f32x4 mma16(f32x4 c, Frag a, Frag b) {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], c, 0, 0, 0);
+        return c;
+    }
+    static __device__ __forceinline__ f32x4 mma_vec(f32x4 c, Vec a, Vec b) { return mma16(c, a, b); }
+};
+
+template <class T>
+__device__ __forceinline__ typename Traits<T>::Frag frag_from_f32(f32x4 v) {
+    typename Traits<T>::Frag f;
+    f[0] = Traits<T>::from_f32(v[0]);
+    f[1] = Traits<T>::from_f32(v[1]);
+    f[2] = Traits<T>::from_f32(v[2]);
+    f[3] = Traits<T>::from_f32(v[3]);
+    return f;
+}
+
+template <class T>
+__device__ __forceinline__ f32x4 frag_to_f32(typename Traits<T>::Frag f) {
+    f32x4 v;
+    v[0] = Traits<T>::to_f32(f[0]);
+    v[1] = Traits<T>::to_f32(f[1]);
+    v[2] = Traits<T>::to_f32(f[2]);
+    v[3] = Traits<T>::to_f32(f[3]);
+    return v;
+}
+
+// v = hi + lo with hi = round(v) and lo = round(v - hi), both in the storage type.
+template <class T>
+__device__ __forceinline__ void frag_split(f32x4 v, typename Traits<T>::Frag& hi, typename Traits<T>::Frag& lo) {
+    hi = frag_from_f32<T>(v);
+    const f32x4 h = frag_to_f32<T>(hi);
+    lo = frag_from_f32<T>(f32x4{v[0] - h[0], v[1] - h[1], v[2] - h[2], v[3] - h[3]});
+}
+
+template <class T>
+__device__ __forceinline__ typename Traits<T>::Frag frag_zero() {
+    typename Traits<T>::Frag f;
+    f[0] = f[1] = f[2] = f[3] = Traits<T>::from_f32(0.0f);
+    return f;
+}
+
+// Elementwise max(v, 0) on a fragment (Eq. (2): the rectifier on Q and K).
+template <class T>
+__device__ __forceinline__ typename Traits<T>::Frag frag_relu(typename Traits<T>::Frag f) {
+    const typename Traits<T>::elem z = Traits<T>::from_f32(0.0f);
+    f[0] = f[0] > z ? f[0] : z;
+    f[1] = f[1] > z ? f[1] : z;
+    f[2] = f[2] > z ? f[2] : z;
+    f[3] = f[3] > z ? f[3] : z;
+    return f;
+}
+
+// 4 consecutive elements (one Frag) to / from memory.  8 bytes for the 16-bit
+// types, 16 bytes for fp32; the address must be aligned to 8 bytes (LDS tiles
+// are padded to 8-byte pixel strides), so fp32 moves as two 8-byte halves.
+template <class T>
+__device__ __forceinline__ typename Traits<T>::Frag load_frag(const void* p) {
+    if constexpr (sizeof(T) == 2) {
+        return __builtin_bit_cast(typename Traits<T>::Frag, *(const u32x2*)p);
+    } else {
+        const u32x2 lo = ((const u32x2*)p)[0], hi = ((const u32x2*)p)[1];
+        u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+        return __builtin_bit_cast(typename Traits<T>::Frag, v);
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void store_frag(void* p, typename Traits<T>::Frag f) {
+    if constexpr (sizeof(T) == 2) {
+        *(u32x2*)p = __builtin_bit_cast(u32x2, f);
+    } else {
+        const u32x4 v = __builtin_bit_cast(u32x4, f);
+        ((u32x2*)p)[0] = u32x2{v[0], v[1]};
+        ((u32x2*)p)[1] = u32x2{v[2], v[3]};
+    }
+}
+
+// Workgroup id -> logical id so that consecutive logical ids run on the same
+// XCD.  The hardware deals workgroups round-robin over the 8 XCDs (each with
+// its own L2); neighbours in the logical order share cache lines, so they
+// should share an L2.  Identity when the grid is not a multiple of 8.
+__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned nblocks) {
+    constexpr unsigned kXcd = 8;
+    if (nblocks % kXcd != 0) return bid;
+    return (bid % kXcd) * (nblocks / kXcd) + bid / kXcd;
+}
+
+}  // namespace msla

@@ -1,0 +1,61 @@
+// Host-side launchers of the gfx950 kernels (internal to the library; the
+// public boundary is include/msla.h).  Every pointer is a device pointer.
+// dt: 0 fp32, 1 fp16, 2 bf16 (the values of msla_dtype).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace msla {
+
+// y[n, o] = sum_c x[n, c] * w[o, c]
+hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in,
+                         int c_out, hipStream_t stream);
+
+// The Q/K/V projection with a split destination: output channel (h*3+t)*16+e goes to
+//   t = 0: q_ms[n * q_ms_stride + h*16 + e]       (branch-0 columns of the multi-scale Q map)
+//   t > 0: kv_raw[n * 2*Ct + h*32 + (t-1)*16 + e]
+hipError_t launch_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
+                              void* kv_raw, long n_tokens, int c_in, int heads, hipStream_t stream);
+
+struct AggregateArgs {
+    // raw Q, K, V maps: element (token n, head h, channel e) of map m lives at
+    // m + n * m_ts + h * m_hs + e   (strides in elements)
+    const void *q, *k, *v;
+    long q_ts, k_ts, v_ts;
+    int q_hs, k_hs, v_hs;
+    const void* w_dw;        // [3*Ct, ks, ks] of this scale
+    const void* w_gpw;       // [3*Ct, 16] of this scale
+    void* q_ms;              // [T, S*Ct] multi-scale Q map (written: this branch; branch 0 if copy_raw_q)
+    float* partials;         // [B, S, heads, nchunks, 272] per-workgroup partial states
+    int B, H, W, heads, S;
+    int ks;                  // 3 or 5
+    int branch;              // 1 + index of this scale
+    int nchunks, tiles_per_chunk;
+    int do_raw;              // also accumulate the branch-0 state from the raw K, V
+    int copy_raw_q;          // also copy the raw Q into the branch-0 columns of q_ms
+};
+hipError_t launch_aggregate(int dt, const AggregateArgs& a, hipStream_t stream);
+
+// Raw-branch-only variant for n_scales == 0 (no convolution): state of branch 0, optional Q copy.
+hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream);
+
+// Sums the per-workgroup partial states in a fixed order and emits
+//   kv32    [n_states, 16, 17] fp32 (the state of Eq. (3))
+//   kvfrag  [n_states, 2, 64, 16 bytes] the state laid out as MFMA operands
+//   kvscale [n_states] the power of two the operands were scaled by
+hipError_t launch_state_finalize(int dt, const float* partials, float* kv32, void* kvfrag, float* kvscale,
+                                 int n_states, int nchunks, hipStream_t stream);
+
+// att[n, m*16 + f] for every head-branch m of q_ms (Eq. (3), last line)
+hipError_t launch_apply(int dt, const void* q_ms, const void* kvfrag, const float* kvscale, void* att,
+                        long n_tokens, int tokens_per_image, int n_hb, float eps, hipStream_t stream);
+
+// out[n, c] = sum_m att[n, m] * w_proj[c, m] with att produced on the fly
+hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
+                                const void* w_proj, void* out, long n_tokens, int tokens_per_image,
+                                int n_hb, int c_out, float eps, hipStream_t stream);
+
+constexpr int kAggTileH = 8;
+constexpr int kAggTileW = 32;
+
+}  // namespace msla
