@@ -60,6 +60,10 @@ struct GemmTile {
     static __device__ __forceinline__ void mma(f32x4 (&acc)[4][4], const char* ldsR, const char* ldsC,
                                                int wr, int wc) {
         const int x = lane_id() & 15, q = lane_id() >> 4;
+#ifdef MSLA_EXP_NOMMA
+        if (ldsR[0] == 77 && ldsC[1] == 78) acc[0][0][0] += 1.f;
+        return;
+#endif
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             Vec a[4], b[4];
@@ -98,7 +102,11 @@ struct GemmTile {
 #pragma unroll
             for (int io = 0; io < 4; ++io) {
                 const int oc = oc0 + wr * 64 + io * 16 + q * 4;
+#ifdef MSLA_EXP_NOSTORE
+                if (oc < oc_limit && acc[io][jt][0] == 12345.678f) ep(tok, oc, acc[io][jt]);
+#else
                 if (oc < oc_limit) ep(tok, oc, acc[io][jt]);
+#endif
             }
         }
     }

@@ -1,0 +1,370 @@
+// Multi-scale token aggregation fused with the state of Eq. (3), 16-bit storage
+// types, with the depthwise convolution on the matrix cores.
+//
+// Section 3.1 (last paragraph): every Q, K and V map of every head is aggregated
+// over nearby tokens by a small depthwise convolution followed by a grouped 1x1
+// convolution (3*heads groups of d channels); Eq. (3) then needs, per image /
+// branch / head, only  KV = sum_n relu(K_n)^T [V_n, 1].
+//
+// On the vector ALUs the depthwise taps (25 fp32 FMAs per output, packed fp32
+// off) cost more time than the kernel's HBM traffic.  A depthwise convolution
+// has no contraction over channels, but along one image row it is a banded
+// (Toeplitz) matrix product: out[x0+i] = sum_k w[k-i] in[x0-p+k].  The
+// 16-block 4x4x4 MFMA does 16 such independent 4x4 products at once, one block
+// per channel of a (head, Q/K/V) group:
+//     A_b[i][k] = w[b][u][4s + k - i]      (filter row u, k-step s; zero outside the band)
+//     B_b[k][j] = in[b][row][x0(j) - p + 4s + k]   (4 x-blocks j of one image row)
+//     D_b[i][j] += A_b B_b                 (4 outputs x0(j)+i of channel b)
+// A wave sweeps a 16-token-wide strip downwards: each input row is read once
+// from LDS and multiplied into the (up to) k rolling accumulators of the
+// output rows it touches.  The Toeplitz operands of a head's 48 channels are
+// built once per workgroup and stay in registers.
+//
+// The halo tile is kept channel-planar in LDS ([channel][row][x], x contiguous),
+// which is what B_b wants; the global maps are token-major, so staging goes
+// through an MFMA with an identity (selection) matrix that hands each lane 4
+// consecutive tokens of one channel -- exact, and as a by-product those are the
+// operands of the raw branch's  KV += relu(K)^T V.
+//
+// After the depthwise pass a lane holds 4 tokens of one channel.  V is only
+// permuted across lanes (ds_bpermute) into the KV operand layout; its grouped
+// 1x1 is linear and is applied once to the accumulated 16x16 state at the end:
+//     KV[e][f] = sum_c (sum_n relu(K_n[e]) dwV_n[c]) w_gpw[f][c].
+// K and Q are transposed through a small per-wave LDS buffer into the operand
+// layout of the grouped 1x1 (one 16x16x16 MFMA per 16 tokens), K's result being
+// the row operand of KV, Q's (transposed product) going to HBM.
+#include "msla_device.h"
+#include "msla_kernels.h"
+
+namespace msla {
+namespace {
+
+constexpr int MTH = kAggMfmaTileH;   // 16 tile rows: two halves of 8, one per wave pair
+constexpr int MTW = kAggMfmaTileW;   // 32 tile columns: two 16-token strips
+constexpr int kThreads = 256;
+
+template <int KS>
+struct MLds {
+    static constexpr int P = (KS - 1) / 2;
+    static constexpr int LH = MTH + 2 * P, LW = MTW + 2 * P;
+    static constexpr int kRowBytes = 72;                       // 36 columns, 8-byte aligned
+    static constexpr int kChanRaw = LH * kRowBytes;
+    // channel stride = 8 banks mod 32, so the 64 lanes' 8-byte reads (16 channels x 4 x-blocks)
+    // spread evenly over the banks
+    static constexpr int kChanBytes = kChanRaw + ((8 - (kChanRaw / 4) % 32 + 32) % 32) * 4;
+    static constexpr int kPlanarBytes = 48 * kChanBytes;
+    static constexpr int kTokStride = 80;                      // transposition buffer: 16 tokens x 16 fp32 (+pad)
+    static constexpr int kTransBytes = 16 * kTokStride;
+    static constexpr int kBytes = kPlanarBytes + 4 * kTransBytes;
+    static_assert(LW <= 36 && (kChanBytes / 4) % 32 == 8, "LDS layout");
+};
+
+template <class T> struct M4;
+template <> struct M4<_Float16> {
+    static __device__ __forceinline__ f32x4 mma(f16x4 a, f16x4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct M4<__bf16> {
+    static __device__ __forceinline__ f32x4 mma(bf16x4 a, bf16x4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(i16x4, a), __builtin_bit_cast(i16x4, b), c,
+                                                      0, 0, 0);
+    }
+};
+
+// Compiler-level ordering of LDS traffic inside one wave (the hardware already
+// executes a wave's LDS instructions in order).
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <class T, int KS>
+__global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs a) {
+    typedef Traits<T> Tr;
+    typedef typename Tr::Frag Frag;
+    typedef typename Tr::Vec Vec;
+    typedef MLds<KS> L;
+    constexpr int P = L::P;
+    constexpr int NS = 2;                 // k-steps of 4 input columns: 4 + 2P <= 8
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char* planar = lds;
+    float* red = (float*)lds;             // reused after the last tile
+
+    const unsigned Lid = xcd_remap(blockIdx.x, gridDim.x);
+    const int h = Lid % a.heads;
+    const int chunk = (Lid / a.heads) % a.nchunks;
+    const int b = Lid / (a.heads * a.nchunks);
+    const int Ct = a.heads * 16;
+    const long N = (long)a.H * a.W;
+    const long img_tok0 = (long)b * N;
+
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int x16 = lane & 15, q = lane >> 4;      // 16x16 MFMA view of the lane
+    const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block (channel), row/column inside it
+    char* trans = lds + L::kPlanarBytes + wave * L::kTransBytes;
+
+    const T* wdw = (const T*)a.w_dw + (long)h * 48 * KS * KS;
+    const T* wgp = (const T*)a.w_gpw + (long)h * 48 * 16;
+
+    // Toeplitz operands of the three 16-channel groups: lane (channel blk, output i = sub)
+    Frag toep[3][KS][NS];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+        for (int u = 0; u < KS; ++u)
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int v = 4 * s + k - sub;
+                    T val = Tr::from_f32(0.f);
+                    if (v >= 0 && v < KS) val = wdw[((t * 16 + blk) * KS + u) * KS + v];
+                    toep[t][u][s][k] = val;
+                }
+    // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
+    const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
+    const Frag gpw_k = load_frag<T>(wgp + (1 * 16 + x16) * 16 + q * 4);
+    // selection matrices for staging: ident picks channel x16 out of 16; selk / selv pick it out of
+    // the 32 contraction slots {K 0..15, V 0..15} of a 16-byte K|V load
+    Frag ident;
+    Vec selk, selv;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ident[r] = Tr::from_f32(x16 == q * 4 + r ? 1.0f : 0.0f);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        selk[r] = Tr::from_f32(q * 8 + r == x16 ? 1.0f : 0.0f);
+        selv[r] = Tr::from_f32(q * 8 + r == 16 + x16 ? 1.0f : 0.0f);
+    }
+
+    const T* qmap = (const T*)a.q + (long)h * a.q_hs;
+    const T* kmap = (const T*)a.k + (long)h * a.k_hs;     // V follows K: 32 contiguous channels
+    T* q_ms = (T*)a.q_ms;
+    const long q_ms_ts = (long)a.S * Ct;
+
+    f32x4 kv_agg = {0.f, 0.f, 0.f, 0.f}, kv_raw = {0.f, 0.f, 0.f, 0.f};
+    float ks_agg = 0.f, ks_raw = 0.f;
+    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+
+    const int tiles_x = (a.W + MTW - 1) / MTW, tiles_y = (a.H + MTH - 1) / MTH;
+    const int n_tiles = tiles_x * tiles_y;
+    const int tile_begin = chunk * a.tiles_per_chunk;
+    const int tile_end = min(n_tiles, tile_begin + a.tiles_per_chunk);
+
+    const int strip = wave & 1, half = wave >> 1;
+
+    for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
+        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+        __syncthreads();   // previous tile fully consumed
+
+        // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way
+        // unit = (LDS row ly, 16 columns from lx0, {K|V pair, Q}); 3 column groups per row
+        for (int unit = wave; unit < L::LH * 3 * 2; unit += 4) {
+            const int is_q = unit & 1;
+            const int cg = (unit >> 1) % 3, ly = (unit >> 1) / 3;
+            const int lx0 = cg * 16;
+            const int gy = ty0 - P + ly;
+            // lane (token x16, q) loads its token's channels
+            const int gx_ld = tx0 - P + lx0 + x16;
+            const bool in_img = gy >= 0 && gy < a.H && gx_ld >= 0 && gx_ld < a.W && lx0 + x16 < L::LW;
+            const long tok_ld = img_tok0 + (long)gy * a.W + gx_ld;
+            // D lane (channel x16, q) receives tokens lx0 + 4q + r
+            const int lxq = lx0 + 4 * q;
+            const bool row_interior = ly >= P && ly < P + MTH;
+            if (is_q) {
+                Frag qf = frag_zero<T>();
+                if (in_img) qf = load_frag<T>(qmap + tok_ld * a.q_ts + q * 4);
+                const Frag d = frag_from_f32<T>(Tr::mma16(z, qf, ident));
+                if (lxq + 3 < L::kRowBytes / 2)
+                    store_frag<T>(planar + (0 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, d);
+                if (a.copy_raw_q && in_img && row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW)
+                    store_frag<T>(q_ms + tok_ld * q_ms_ts + h * 16 + q * 4, qf);
+            } else {
+                u32x4 raw = {0u, 0u, 0u, 0u};
+                if (in_img) raw = *(const u32x4*)(kmap + tok_ld * a.k_ts + q * 8);
+                const Vec kvv = __builtin_bit_cast(Vec, raw);
+                const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
+                const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
+                if (lxq + 3 < L::kRowBytes / 2) {
+                    store_frag<T>(planar + (1 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, dk);
+                    store_frag<T>(planar + (2 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, dv);
+                }
+                if (a.do_raw && row_interior) {
+                    // raw branch: tokens of this tile's interior only (each token belongs to one tile)
+                    Frag rk = frag_relu<T>(dk);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (lxq + r < P || lxq + r >= P + MTW) rk[r] = Tr::from_f32(0.f);
+                    const f32x4 rf = frag_to_f32<T>(rk);
+                    ks_raw += (rf[0] + rf[1]) + (rf[2] + rf[3]);
+                    kv_raw = Tr::mma16(kv_raw, rk, dv);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---------------- depthwise sweep: this wave's strip (16 columns) x half (8 rows)
+        const int col0 = 16 * strip + 4 * sub;            // interior column of this lane's x-block
+        const int gy0 = ty0 + 8 * half;
+        const int gx0 = tx0 + col0;
+        Frag aggK[8], aggK_lo[8];
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int t = (pass == 0) ? 1 : (pass == 1) ? 2 : 0;     // K, V, Q
+            const char* src = planar + (t * 16 + blk) * L::kChanBytes + (8 * half) * L::kRowBytes + col0 * 2;
+            f32x4 acc[KS];
+#pragma unroll
+            for (int i = 0; i < KS; ++i) acc[i] = z;
+#pragma unroll
+            for (int r = 0; r < 8 + 2 * P; ++r) {
+                const Frag d0 = load_frag<T>(src + r * L::kRowBytes);
+                const Frag d1 = load_frag<T>(src + r * L::kRowBytes + 8);
+#pragma unroll
+                for (int u = 0; u < KS; ++u) {
+                    const int y = r - u;
+                    if (y < 0 || y >= 8) continue;
+                    acc[y % KS] = M4<T>::mma(toep[t][u][0], d0, acc[y % KS]);
+                    acc[y % KS] = M4<T>::mma(toep[t][u][1], d1, acc[y % KS]);
+                }
+                const int y = r - (KS - 1);
+                if (y < 0) continue;
+                // ---- output row y of 16 channels x 16 tokens is complete: lane (channel blk, x-block sub)
+                // holds the 4 tokens gx0..gx0+3 of image row gy0 + y
+                f32x4 o = acc[y % KS];
+                acc[y % KS] = z;
+                const int gy = gy0 + y;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;      // tokens outside the image contribute nothing
+                if (t == 2) {
+                    // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
+                    f32x4 vf;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vf[i] = __shfl(o[i], 4 * x16 + q);
+                    if constexpr (Tr::kHiLo) {
+                        Frag vh, vl;
+                        frag_split<T>(vf, vh, vl);
+                        kv_agg = Tr::mma16(kv_agg, aggK[y], vh);
+                        kv_agg = Tr::mma16(kv_agg, aggK[y], vl);
+                        kv_agg = Tr::mma16(kv_agg, aggK_lo[y], vh);
+                    } else {
+                        kv_agg = Tr::mma16(kv_agg, aggK[y], frag_from_f32<T>(vf));
+                    }
+                } else {
+                    // K, Q: 16 tokens x 16 channels -> lane (token 4*xblock + i, q) with channels 4q..4q+3
+                    wave_lds_fence();
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) *(float*)(trans + (4 * sub + i) * L::kTokStride + blk * 4) = o[i];
+                    wave_lds_fence();
+                    const f32x4 tq = *(const f32x4*)(trans + x16 * L::kTokStride + q * 16);
+                    Frag dwf, dwf_lo;
+                    if constexpr (Tr::kHiLo) frag_split<T>(tq, dwf, dwf_lo);
+                    else dwf = frag_from_f32<T>(tq);
+                    if (t == 1) {
+                        f32x4 kf = Tr::mma16(z, dwf, gpw_k);
+                        if constexpr (Tr::kHiLo) kf = Tr::mma16(kf, dwf_lo, gpw_k);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) kf[c] = fmaxf(kf[c], 0.f);      // Eq. (2): relu(K)
+                        ks_agg += (kf[0] + kf[1]) + (kf[2] + kf[3]);
+                        if constexpr (Tr::kHiLo) frag_split<T>(kf, aggK[y], aggK_lo[y]);
+                        else aggK[y] = frag_from_f32<T>(kf);
+                    } else {
+                        f32x4 qq = Tr::mma16(z, gpw_q, dwf);
+                        if constexpr (Tr::kHiLo) qq = Tr::mma16(qq, gpw_q, dwf_lo);
+                        // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3
+                        const int gx = tx0 + 16 * strip + x16;
+                        if (gy < a.H && gx < a.W)
+                            store_frag<T>(q_ms + (img_tok0 + (long)gy * a.W + gx) * q_ms_ts + (long)a.branch * Ct +
+                                              h * 16 + q * 4,
+                                          frag_from_f32<T>(qq));
+                    }
+                }
+            }
+        }
+    }
+
+    // ---------------- workgroup partial state
+    ks_agg += __shfl_xor(ks_agg, 16);
+    ks_agg += __shfl_xor(ks_agg, 32);
+    ks_raw += __shfl_xor(ks_raw, 16);
+    ks_raw += __shfl_xor(ks_raw, 32);
+    __syncthreads();   // tile memory is dead from here on
+    // per wave: [which][lane] accumulator quads, then [which][16] Ksum; which 0 = aggregated (V before
+    // its grouped 1x1), 1 = raw
+    constexpr int kWaveFloats = 2 * 256 + 2 * 16;
+    float* msum = red + 4 * kWaveFloats;          // [16][16] summed pre-1x1 state of the aggregated branch
+    {
+        float* mine = red + wave * kWaveFloats;
+        *(f32x4*)(mine + lane * 4) = kv_agg;
+        *(f32x4*)(mine + 256 + lane * 4) = kv_raw;
+        if (q == 0) {
+            mine[512 + x16] = ks_agg;
+            mine[512 + 16 + x16] = ks_raw;
+        }
+    }
+    __syncthreads();
+    {
+        // M[e][c] of the aggregated branch, summed over the waves: lane (c, e / 4), element e % 4
+        const int j = threadIdx.x;
+        const int e = j >> 4, c = j & 15;
+        const int src = ((e >> 2) * 16 + c) * 4 + (e & 3);
+        msum[j] = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < 2 * kStateSize; j += kThreads) {
+        const int which = j / kStateSize, idx = j - which * kStateSize;   // 0: aggregated, 1: raw
+        if (which == 1 && !a.do_raw) continue;
+        const int e = idx / 17, f = idx - e * 17;
+        float s;
+        if (f == 16) {
+            const int src = 512 + which * 16 + e;
+            s = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+        } else if (which == 1) {
+            const int src = 256 + ((e >> 2) * 16 + f) * 4 + (e & 3);
+            s = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+        } else {
+            // the grouped 1x1 of V, applied to the summed state: KV[e][f] = sum_c M[e][c] w_gpw[f][c]
+            const T* wv = wgp + (2 * 16 + f) * 16;
+            s = 0.f;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) s = fmaf(msum[e * 16 + c], Tr::to_f32(wv[c]), s);
+        }
+        const int branch = which == 0 ? a.branch : 0;
+        a.partials[((((long)b * a.S + branch) * a.heads + h) * a.nchunks + chunk) * kStateSize + idx] = s;
+    }
+}
+
+template <class T, int KS>
+hipError_t run_ks(const AggregateArgs& a, unsigned nblocks, hipStream_t stream) {
+    constexpr int kLds = MLds<KS>::kBytes;
+    const hipError_t e = hipFuncSetAttribute((const void*)aggregate_mfma_kernel<T, KS>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((aggregate_mfma_kernel<T, KS>), dim3(nblocks), dim3(kThreads), kLds, stream, a);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t run(const AggregateArgs& a, hipStream_t stream) {
+    const long nblocks = (long)a.B * a.heads * a.nchunks;
+    if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    // the kernel reads K and V of a token as one 32-channel run
+    if ((const char*)a.v != (const char*)a.k + 16 * sizeof(T) || a.v_ts != a.k_ts || a.v_hs != a.k_hs)
+        return hipErrorInvalidValue;
+    if (a.ks == 3) return run_ks<T, 3>(a, (unsigned)nblocks, stream);
+    if (a.ks == 5) return run_ks<T, 5>(a, (unsigned)nblocks, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream) {
+    switch (dt) {
+        case 1: return run<_Float16>(a, stream);
+        case 2: return run<__bf16>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace msla

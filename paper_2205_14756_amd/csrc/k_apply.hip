@@ -14,8 +14,16 @@
 #include "gemm_tile.h"
 #include "msla_kernels.h"
 
+#ifndef MSLA_APPLY_WR
+#define MSLA_APPLY_WR 4
+#define MSLA_APPLY_WC 2
+#endif
+
 namespace msla {
 namespace {
+
+template <class T>
+using ApplyTile = GemmTile<T, MSLA_APPLY_WR, MSLA_APPLY_WC>;
 
 // q: channels 4q..4q+3 of this lane's token (raw, not yet rectified).
 // state: the 2048-byte operand block of (image, head-branch).  eps_s = eps * scale.
@@ -78,15 +86,18 @@ __global__ __launch_bounds__(256) void apply_kernel(const T* __restrict__ q_ms, 
 // prefetch.  For bf16 the attention rows go to LDS as a hi and a lo tile (two
 // MFMA passes), since 8 significant bits would cost half the error budget.
 template <class T>
-__global__ __launch_bounds__(512) void apply_project_kernel(const T* __restrict__ q_ms,
+__global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(const T* __restrict__ q_ms,
                                                             const char* __restrict__ kvfrag,
                                                             const float* __restrict__ kvscale,
                                                             const T* __restrict__ w_proj, T* __restrict__ out,
                                                             int N, int n_hb, int c_out, int blocks_per_image,
                                                             int n_rb, float eps) {
-    typedef GemmTile<T, 4, 2> G;
+    typedef ApplyTile<T> G;
     typedef typename Traits<T>::Frag Frag;
     constexpr int HB = G::BK / 16;   // head-branches per iteration
+    constexpr int kWaves = G::kThreads / 64;
+    constexpr int TG = (G::BC / 16) / kWaves;   // 16-token groups per wave for the attention rows
+    static_assert(TG >= 1 && TG * kWaves * 16 == G::BC, "token groups must divide over the waves");
     constexpr bool kHiLo = Traits<T>::kHiLo;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* ldsR = lds;
@@ -100,39 +111,53 @@ __global__ __launch_bounds__(512) void apply_project_kernel(const T* __restrict_
     const int n0 = (tb % blocks_per_image) * G::BC;
     const int oc0 = rb * G::BR;
     const int wave = threadIdx.x >> 6;
-    const int wr = wave & 3, wc = wave >> 2;
+    const int wr = wave % MSLA_APPLY_WR, wc = wave / MSLA_APPLY_WR;
     const int x16 = lane_id() & 15, q = lane_id() >> 4;
     const int K = n_hb * 16;
 
-    // this lane's token for the attention rows: token group = wave
-    const int n_mine = n0 + wave * 16 + x16;
-    const bool ok = n_mine < N;
-    const T* q_row = q_ms + ((long)b * N + n_mine) * K + q * 4;
+    // this lane's tokens for the attention rows: token groups wave, wave + kWaves, ...
+    bool ok[TG];
+    const T* q_row[TG];
+#pragma unroll
+    for (int g = 0; g < TG; ++g) {
+        const int n_mine = n0 + (g * kWaves + wave) * 16 + x16;
+        ok[g] = n_mine < N;
+        q_row[g] = q_ms + ((long)b * N + n_mine) * K + q * 4;
+    }
     const long sid0 = (long)b * n_hb;
 
     f32x4 acc[4][4];
     G::zero(acc);
     u32x4 rw[G::kVecR];
-    Frag qreg[HB];
+    Frag qreg[TG][HB];
     G::load_global(rw, w_proj, oc0, c_out, K, 0, K);
 #pragma unroll
-    for (int j = 0; j < HB; ++j) qreg[j] = (ok && j < n_hb) ? load_frag<T>(q_row + j * 16) : frag_zero<T>();
+    for (int g = 0; g < TG; ++g)
+#pragma unroll
+        for (int j = 0; j < HB; ++j)
+            qreg[g][j] = (ok[g] && j < n_hb) ? load_frag<T>(q_row[g] + j * 16) : frag_zero<T>();
 
     for (int k0 = 0; k0 < K; k0 += G::BK) {
         G::store_lds(ldsR, rw);
         const int m0 = k0 >> 4;
 #pragma unroll
         for (int j = 0; j < HB; ++j) {
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-            if (m0 + j < n_hb) o = att_unit<T>(qreg[j], kvfrag + (sid0 + m0 + j) * 2048, eps * kvscale[sid0 + m0 + j]);
-            const int off = (wave * 16 + x16) * G::kRowStride + (j * 16 + q * 4) * (int)sizeof(T);
-            if constexpr (kHiLo) {
-                Frag hi, lo;
-                frag_split<T>(o, hi, lo);
-                store_frag<T>(ldsC + off, hi);
-                store_frag<T>(ldsC_lo + off, lo);
-            } else {
-                store_frag<T>(ldsC + off, frag_from_f32<T>(o));
+            const bool live = m0 + j < n_hb;
+            const char* state = kvfrag + (sid0 + m0 + j) * 2048;
+            const float eps_s = live ? eps * kvscale[sid0 + m0 + j] : 0.f;
+#pragma unroll
+            for (int g = 0; g < TG; ++g) {
+                f32x4 o = {0.f, 0.f, 0.f, 0.f};
+                if (live) o = att_unit<T>(qreg[g][j], state, eps_s);
+                const int off = ((g * kWaves + wave) * 16 + x16) * G::kRowStride + (j * 16 + q * 4) * (int)sizeof(T);
+                if constexpr (kHiLo) {
+                    Frag hi, lo;
+                    frag_split<T>(o, hi, lo);
+                    store_frag<T>(ldsC + off, hi);
+                    store_frag<T>(ldsC_lo + off, lo);
+                } else {
+                    store_frag<T>(ldsC + off, frag_from_f32<T>(o));
+                }
             }
         }
         __syncthreads();
@@ -140,8 +165,10 @@ __global__ __launch_bounds__(512) void apply_project_kernel(const T* __restrict_
             G::load_global(rw, w_proj, oc0, c_out, K, k0 + G::BK, K);
             const int m1 = m0 + HB;
 #pragma unroll
-            for (int j = 0; j < HB; ++j)
-                qreg[j] = (ok && m1 + j < n_hb) ? load_frag<T>(q_row + (m1 + j) * 16) : frag_zero<T>();
+            for (int g = 0; g < TG; ++g)
+#pragma unroll
+                for (int j = 0; j < HB; ++j)
+                    qreg[g][j] = (ok[g] && m1 + j < n_hb) ? load_frag<T>(q_row[g] + (m1 + j) * 16) : frag_zero<T>();
         }
         G::mma(acc, ldsR, ldsC, wr, wc);
         if constexpr (kHiLo) G::mma(acc, ldsR, ldsC_lo, wr, wc);
@@ -168,7 +195,7 @@ template <class T>
 hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
                              void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
                              hipStream_t stream) {
-    typedef GemmTile<T, 4, 2> G;
+    typedef ApplyTile<T> G;
     const int bpi = (N + G::BC - 1) / G::BC;
     const int n_rb = (c_out + G::BR - 1) / G::BR;
     const long nblocks = (n_tokens / N) * bpi * n_rb;

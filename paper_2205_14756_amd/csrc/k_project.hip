@@ -4,8 +4,16 @@
 #include "gemm_tile.h"
 #include "msla_kernels.h"
 
+#ifndef MSLA_PROJ_WR
+#define MSLA_PROJ_WR 4
+#define MSLA_PROJ_WC 2
+#endif
+
 namespace msla {
 namespace {
+
+template <class T>
+using ProjTile = GemmTile<T, MSLA_PROJ_WR, MSLA_PROJ_WC>;
 
 template <class T>
 struct PlainStore {
@@ -33,10 +41,10 @@ struct QkvSplitStore {
 };
 
 template <class T, class Epilogue>
-__global__ __launch_bounds__(512) void project_kernel(const T* __restrict__ x, const T* __restrict__ w,
+__global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                       long n_tokens, int c_in, int c_out, int n_rb,
                                                       Epilogue ep) {
-    typedef GemmTile<T, 4, 2> G;
+    typedef ProjTile<T> G;
     __shared__ __attribute__((aligned(16))) char lds[G::kLdsR + G::kLdsC];
     char* ldsR = lds;
     char* ldsC = lds + G::kLdsR;
@@ -47,7 +55,7 @@ __global__ __launch_bounds__(512) void project_kernel(const T* __restrict__ x, c
     const int oc0 = rb * G::BR;
     const long tok0 = cb * G::BC;
     const int wave = threadIdx.x >> 6;
-    const int wr = wave & 3, wc = wave >> 2;
+    const int wr = wave % MSLA_PROJ_WR, wc = wave / MSLA_PROJ_WR;
 
     f32x4 acc[4][4];
     G::zero(acc);
@@ -71,7 +79,7 @@ __global__ __launch_bounds__(512) void project_kernel(const T* __restrict__ x, c
 template <class T, class Epilogue>
 hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, int c_out, Epilogue ep,
                        hipStream_t stream) {
-    typedef GemmTile<T, 4, 2> G;
+    typedef ProjTile<T> G;
     const int n_rb = (c_out + G::BR - 1) / G::BR;
     const long n_cb = (n_tokens + G::BC - 1) / G::BC;
     const long nblocks = n_cb * n_rb;

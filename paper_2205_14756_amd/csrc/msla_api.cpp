@@ -48,14 +48,19 @@ msla_status check_shape(int B, int H, int W, int heads, int head_dim, const int*
     s->N = N; s->T = T; s->Ct = heads * 16; s->n_scales = n_scales;
     for (int i = 0; i < n_scales; ++i) s->scales[i] = scales[i];
     // Split each (image, head) over enough workgroups to fill the chip; every
-    // workgroup then emits one partial state.  A "tile" is 8x32 tokens for the
-    // aggregating kernel, 64 consecutive tokens when there is no aggregated scale.
+    // workgroup then emits one partial state.  A "tile" is 8x32 (fp32) or 16x32 (16-bit types)
+    // tokens for the aggregating kernels, 64 consecutive tokens when there is no aggregated scale.
     long tiles;
-    if (n_scales > 0)
+    long target_blocks = 1024;
+    if (n_scales > 0 && dt == MSLA_F32) {
         tiles = (long)((H + msla::kAggTileH - 1) / msla::kAggTileH) * ((W + msla::kAggTileW - 1) / msla::kAggTileW);
-    else
+    } else if (n_scales > 0) {
+        tiles = (long)((H + msla::kAggMfmaTileH - 1) / msla::kAggMfmaTileH) *
+                ((W + msla::kAggMfmaTileW - 1) / msla::kAggMfmaTileW);
+        target_blocks = 512;   // two resident workgroups per CU; each builds its operands once
+    } else {
         tiles = (N + 63) / 64;
-    const long target_blocks = 1024;
+    }
     long want = (target_blocks + (long)B * heads - 1) / ((long)B * heads);
     if (want < 1) want = 1;
     if (want > tiles) want = tiles;
@@ -115,7 +120,9 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
         a.branch = i + 1;
         a.do_raw = (i == 0);
         a.copy_raw_q = (i == 0) ? copy_raw_q : 0;
-        if (msla::launch_aggregate((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
+        const hipError_t e_launch = (dt == MSLA_F32) ? msla::launch_aggregate((int)dt, a, stream)
+                                                     : msla::launch_aggregate_mfma((int)dt, a, stream);
+        if (e_launch != hipSuccess) return MSLA_ERR_LAUNCH;
     }
     if (event_before_finalize &&
         hipEventRecord(static_cast<hipEvent_t>(event_before_finalize), stream) != hipSuccess)

@@ -36,6 +36,10 @@ struct AggregateArgs {
 };
 hipError_t launch_aggregate(int dt, const AggregateArgs& a, hipStream_t stream);
 
+// Same contract for the 16-bit storage types, depthwise convolution on the matrix cores
+// (16 x 32-token tiles; needs v == k + 16 elements with equal strides).
+hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream);
+
 // Raw-branch-only variant for n_scales == 0 (no convolution): state of branch 0, optional Q copy.
 hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream);
 
@@ -55,7 +59,9 @@ hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, co
                                 const void* w_proj, void* out, long n_tokens, int tokens_per_image,
                                 int n_hb, int c_out, float eps, hipStream_t stream);
 
-constexpr int kAggTileH = 8;
+constexpr int kAggTileH = 8;        // vector-ALU kernel (fp32 storage)
 constexpr int kAggTileW = 32;
+constexpr int kAggMfmaTileH = 16;   // matrix-core kernel (fp16 / bf16 storage)
+constexpr int kAggMfmaTileW = 32;
 
 }  // namespace msla

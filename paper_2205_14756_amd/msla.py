@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmsla.so")
+# MSLA_LIBRARY_PATH lets a tuning run point at another build of the same library
+LIB_PATH = os.environ.get("MSLA_LIBRARY_PATH") or os.path.join(_HERE, "libmsla.so")
 
 MSLA_OK = 0
 MSLA_ERR_INVALID_ARG = -1
