@@ -159,46 +159,71 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         __syncthreads();   // previous tile fully consumed
 
         // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way
-        // unit = (LDS row ly, 16 columns from lx0, {K|V pair, Q}); 3 column groups per row
-        for (int unit = wave; unit < L::LH * 3 * 2; unit += 4) {
-            const int is_q = unit & 1;
-            const int cg = (unit >> 1) % 3, ly = (unit >> 1) / 3;
-            const int lx0 = cg * 16;
-            const int gy = ty0 - P + ly;
-            // lane (token x16, q) loads its token's channels
-            const int gx_ld = tx0 - P + lx0 + x16;
-            const bool in_img = gy >= 0 && gy < a.H && gx_ld >= 0 && gx_ld < a.W && lx0 + x16 < L::LW;
-            const long tok_ld = img_tok0 + (long)gy * a.W + gx_ld;
-            // D lane (channel x16, q) receives tokens lx0 + 4q + r
-            const int lxq = lx0 + 4 * q;
-            const bool row_interior = ly >= P && ly < P + MTH;
-            if (is_q) {
-                Frag qf = frag_zero<T>();
-                if (in_img) qf = load_frag<T>(qmap + tok_ld * a.q_ts + q * 4);
-                const Frag d = frag_from_f32<T>(Tr::mma16(z, qf, ident));
-                if (lxq + 3 < L::kRowBytes / 2)
-                    store_frag<T>(planar + (0 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, d);
-                if (a.copy_raw_q && in_img && row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW)
-                    store_frag<T>(q_ms + tok_ld * q_ms_ts + h * 16 + q * 4, qf);
-            } else {
-                u32x4 raw = {0u, 0u, 0u, 0u};
-                if (in_img) raw = *(const u32x4*)(kmap + tok_ld * a.k_ts + q * 8);
-                const Vec kvv = __builtin_bit_cast(Vec, raw);
-                const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
-                const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
-                if (lxq + 3 < L::kRowBytes / 2) {
-                    store_frag<T>(planar + (1 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, dk);
-                    store_frag<T>(planar + (2 * 16 + x16) * L::kChanBytes + ly * L::kRowBytes + lxq * 2, dv);
-                }
-                if (a.do_raw && row_interior) {
-                    // raw branch: tokens of this tile's interior only (each token belongs to one tile)
-                    Frag rk = frag_relu<T>(dk);
+        // Halo rows are dealt to the waves round-robin, two rows per step so that 12 loads are in
+        // flight before the first is consumed.  A row has 3 groups of 16 columns; lane (token x16, q)
+        // loads its token's 4 Q channels and 8 of its 32 K|V channels, and after the selection MFMA
+        // lane (channel x16, q) holds tokens lx0 + 4q .. + 3 of that channel.
+        constexpr int kRowsPerWave = (L::LH + 3) / 4;
+#pragma unroll 1
+        for (int it = 0; it < kRowsPerWave; it += 2) {
+            Frag qf[2][3];
+            u32x4 kvr[2][3];
+            bool tok_ok[2][3];
+            long tok_row[2];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (lxq + r < P || lxq + r >= P + MTW) rk[r] = Tr::from_f32(0.f);
-                    const f32x4 rf = frag_to_f32<T>(rk);
-                    ks_raw += (rf[0] + rf[1]) + (rf[2] + rf[3]);
-                    kv_raw = Tr::mma16(kv_raw, rk, dv);
+            for (int rr = 0; rr < 2; ++rr) {
+                const int ly = wave + 4 * (it + rr);
+                const int gy = ty0 - P + ly;
+                const bool row_ok = ly < L::LH && gy >= 0 && gy < a.H;
+                tok_row[rr] = img_tok0 + (long)gy * a.W;
+#pragma unroll
+                for (int cg = 0; cg < 3; ++cg) {
+                    const int lx = cg * 16 + x16;
+                    const int gx = tx0 - P + lx;
+                    const bool ok = row_ok && gx >= 0 && gx < a.W && lx < L::LW;
+                    tok_ok[rr][cg] = ok;
+                    qf[rr][cg] = frag_zero<T>();
+                    kvr[rr][cg] = u32x4{0u, 0u, 0u, 0u};
+                    if (ok) {
+                        qf[rr][cg] = load_frag<T>(qmap + (tok_row[rr] + gx) * a.q_ts + q * 4);
+                        kvr[rr][cg] = *(const u32x4*)(kmap + (tok_row[rr] + gx) * a.k_ts + q * 8);
+                    }
+                }
+            }
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int ly = wave + 4 * (it + rr);
+                if (ly >= L::LH) break;
+                const bool row_interior = ly >= P && ly < P + MTH;
+                char* dst_row = planar + x16 * L::kChanBytes + ly * L::kRowBytes + q * 8;
+#pragma unroll
+                for (int cg = 0; cg < 3; ++cg) {
+                    const int lx0 = cg * 16;
+                    const bool writes = cg < 2 || q == 0;       // the third group only has columns 32..35
+                    const Frag dq = frag_from_f32<T>(Tr::mma16(z, qf[rr][cg], ident));
+                    const Vec kvv = __builtin_bit_cast(Vec, kvr[rr][cg]);
+                    const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
+                    const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
+                    if (writes) {
+                        store_frag<T>(dst_row + lx0 * 2, dq);
+                        store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
+                        store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
+                    }
+                    if (a.copy_raw_q && row_interior && tok_ok[rr][cg] && lx0 + x16 >= P && lx0 + x16 < P + MTW)
+                        store_frag<T>(q_ms + (tok_row[rr] + tx0 - P + lx0 + x16) * q_ms_ts + h * 16 + q * 4,
+                                      qf[rr][cg]);
+                    if (a.do_raw && row_interior) {
+                        // raw branch: tokens of this tile's interior only (each token belongs to one tile)
+                        Frag rk = frag_relu<T>(dk);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int lx = lx0 + 4 * q + r;
+                            if (lx < P || lx >= P + MTW) rk[r] = Tr::from_f32(0.f);
+                        }
+                        const f32x4 rf = frag_to_f32<T>(rk);
+                        ks_raw += (rf[0] + rf[1]) + (rf[2] + rf[3]);
+                        kv_raw = Tr::mma16(kv_raw, rk, dv);
+                    }
                 }
             }
         }
