@@ -100,7 +100,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const long N = (long)a.H * a.W;
     const long img_tok0 = (long)b * N;
 
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: row/strip math stays on the SALU
     const int x16 = lane & 15, q = lane >> 4;      // 16x16 MFMA view of the lane
     const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block (channel), row/column inside it
     char* trans = lds + L::kPlanarBytes + wave * L::kTransBytes;
@@ -144,7 +145,13 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const long q_ms_ts = (long)a.S * Ct;
 
     f32x4 kv_agg = {0.f, 0.f, 0.f, 0.f}, kv_raw = {0.f, 0.f, 0.f, 0.f};
-    float ks_agg = 0.f, ks_raw = 0.f;
+    // Ksum of the raw branch rides on the matrix cores as well: relu(K)^T . ones puts
+    // sum_n relu(K_n[e]) into every column, i.e. lane (*, q) element r holds Ksum[4q + r]
+    f32x4 ks_raw4 = {0.f, 0.f, 0.f, 0.f};
+    float ks_agg = 0.f;
+    Frag ones;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ones[r] = Tr::from_f32(1.0f);
     const f32x4 z = {0.f, 0.f, 0.f, 0.f};
 
     const int tiles_x = (a.W + MTW - 1) / MTW, tiles_y = (a.H + MTH - 1) / MTH;
@@ -153,79 +160,102 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const int tile_end = min(n_tiles, tile_begin + a.tiles_per_chunk);
 
     const int strip = wave & 1, half = wave >> 1;
+    // lane part of the staging load addresses: token x16 of a 16-column group, channels of q
+    const long lane_q_off = (long)x16 * a.q_ts + q * 4;
+    const long lane_k_off = (long)x16 * a.k_ts + q * 8;
 
-    for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
+    // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way.
+    // Halo rows are dealt to the waves round-robin and handled two at a time ("batch": 12 loads).
+    // A row has 3 groups of 16 columns; lane (token x16, q) loads its token's 4 Q channels and 8 of
+    // its 32 K|V channels, and after the selection MFMA lane (channel x16, q) holds tokens
+    // lx0 + 4q .. + 3 of that channel.  The loads of the next batch are issued before the current one
+    // is consumed, so they are in flight during its MFMAs.
+    struct Batch {
+        Frag qf[2][3];
+        u32x4 kvr[2][3];
+    };
+    constexpr int kBatches = ((L::LH + 3) / 4 + 1) / 2;
+    static_assert(kBatches == 3, "staging schedule below assumes 3 batches per tile");
+
+    auto issue = [&](int tile_id, int it, Batch& bt) {
         const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
-        __syncthreads();   // previous tile fully consumed
-
-        // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way
-        // Halo rows are dealt to the waves round-robin, two rows per step so that 12 loads are in
-        // flight before the first is consumed.  A row has 3 groups of 16 columns; lane (token x16, q)
-        // loads its token's 4 Q channels and 8 of its 32 K|V channels, and after the selection MFMA
-        // lane (channel x16, q) holds tokens lx0 + 4q .. + 3 of that channel.
-        constexpr int kRowsPerWave = (L::LH + 3) / 4;
-#pragma unroll 1
-        for (int it = 0; it < kRowsPerWave; it += 2) {
-            Frag qf[2][3];
-            u32x4 kvr[2][3];
-            bool tok_ok[2][3];
-            long tok_row[2];
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int ly = wave + 4 * (it + rr);
-                const int gy = ty0 - P + ly;
-                const bool row_ok = ly < L::LH && gy >= 0 && gy < a.H;
-                tok_row[rr] = img_tok0 + (long)gy * a.W;
+        for (int rr = 0; rr < 2; ++rr) {
+            const int ly = wave + 4 * (it + rr);
+            const int gy = ty0 - P + ly;
+            const bool row_ok = ly < L::LH && gy >= 0 && gy < a.H;
+            // wave-uniform row bases; the lane part of the address is loop-invariant
+            const long tok_first = img_tok0 + (long)gy * a.W + (tx0 - P);
+            const T* qrow = qmap + tok_first * a.q_ts;
+            const T* krow = kmap + tok_first * a.k_ts;
 #pragma unroll
-                for (int cg = 0; cg < 3; ++cg) {
-                    const int lx = cg * 16 + x16;
-                    const int gx = tx0 - P + lx;
-                    const bool ok = row_ok && gx >= 0 && gx < a.W && lx < L::LW;
-                    tok_ok[rr][cg] = ok;
-                    qf[rr][cg] = frag_zero<T>();
-                    kvr[rr][cg] = u32x4{0u, 0u, 0u, 0u};
-                    if (ok) {
-                        qf[rr][cg] = load_frag<T>(qmap + (tok_row[rr] + gx) * a.q_ts + q * 4);
-                        kvr[rr][cg] = *(const u32x4*)(kmap + (tok_row[rr] + gx) * a.k_ts + q * 8);
-                    }
+            for (int cg = 0; cg < 3; ++cg) {
+                const int lx = cg * 16 + x16;
+                const int gx = tx0 - P + lx;
+                bt.qf[rr][cg] = frag_zero<T>();
+                bt.kvr[rr][cg] = u32x4{0u, 0u, 0u, 0u};
+                if (row_ok && gx >= 0 && gx < a.W && lx < L::LW) {
+                    bt.qf[rr][cg] = load_frag<T>(qrow + (cg * 16) * a.q_ts + lane_q_off);
+                    bt.kvr[rr][cg] = *(const u32x4*)(krow + (cg * 16) * a.k_ts + lane_k_off);
                 }
             }
+        }
+    };
+
+    auto consume = [&](int tile_id, int it, const Batch& bt) {
+        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int ly = wave + 4 * (it + rr);
-                if (ly >= L::LH) break;
-                const bool row_interior = ly >= P && ly < P + MTH;
-                char* dst_row = planar + x16 * L::kChanBytes + ly * L::kRowBytes + q * 8;
+        for (int rr = 0; rr < 2; ++rr) {
+            const int ly = wave + 4 * (it + rr);
+            if (ly >= L::LH) break;
+            const int gy = ty0 - P + ly;
+            const bool row_interior = ly >= P && ly < P + MTH;
+            const long tok_first = img_tok0 + (long)gy * a.W + (tx0 - P);
+            char* dst_row = planar + x16 * L::kChanBytes + ly * L::kRowBytes + q * 8;
 #pragma unroll
-                for (int cg = 0; cg < 3; ++cg) {
-                    const int lx0 = cg * 16;
-                    const bool writes = cg < 2 || q == 0;       // the third group only has columns 32..35
-                    const Frag dq = frag_from_f32<T>(Tr::mma16(z, qf[rr][cg], ident));
-                    const Vec kvv = __builtin_bit_cast(Vec, kvr[rr][cg]);
-                    const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
-                    const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
-                    if (writes) {
-                        store_frag<T>(dst_row + lx0 * 2, dq);
-                        store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
-                        store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
-                    }
-                    if (a.copy_raw_q && row_interior && tok_ok[rr][cg] && lx0 + x16 >= P && lx0 + x16 < P + MTW)
-                        store_frag<T>(q_ms + (tok_row[rr] + tx0 - P + lx0 + x16) * q_ms_ts + h * 16 + q * 4,
-                                      qf[rr][cg]);
-                    if (a.do_raw && row_interior) {
-                        // raw branch: tokens of this tile's interior only (each token belongs to one tile)
-                        Frag rk = frag_relu<T>(dk);
+            for (int cg = 0; cg < 3; ++cg) {
+                const int lx0 = cg * 16;
+                const bool writes = cg < 2 || q == 0;       // the third group only has columns 32..35
+                const Frag dq = frag_from_f32<T>(Tr::mma16(z, bt.qf[rr][cg], ident));
+                const Vec kvv = __builtin_bit_cast(Vec, bt.kvr[rr][cg]);
+                const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
+                const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
+                if (writes) {
+                    store_frag<T>(dst_row + lx0 * 2, dq);
+                    store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
+                    store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
+                }
+                if (a.copy_raw_q && row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW && gy < a.H &&
+                    tx0 - P + lx0 + x16 < a.W)
+                    store_frag<T>(q_ms + (tok_first + lx0 + x16) * q_ms_ts + h * 16 + q * 4, bt.qf[rr][cg]);
+                if (a.do_raw && row_interior) {
+                    // raw branch: tokens of this tile's interior only (each token belongs to one tile)
+                    Frag rk = frag_relu_bits<T>(dk);
+                    if (cg != 1) {      // the outer column groups contain halo columns
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int lx = lx0 + 4 * q + r;
                             if (lx < P || lx >= P + MTW) rk[r] = Tr::from_f32(0.f);
                         }
-                        const f32x4 rf = frag_to_f32<T>(rk);
-                        ks_raw += (rf[0] + rf[1]) + (rf[2] + rf[3]);
-                        kv_raw = Tr::mma16(kv_raw, rk, dv);
                     }
+                    ks_raw4 = Tr::mma16(ks_raw4, rk, ones);
+                    kv_raw = Tr::mma16(kv_raw, rk, dv);
                 }
             }
+        }
+    };
+
+    for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
+        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+        {
+            Batch b0, b1;
+            issue(tile_id, 0, b0);
+            issue(tile_id, 2, b1);
+            __syncthreads();   // previous tile fully consumed
+            consume(tile_id, 0, b0);
+            issue(tile_id, 4, b0);
+            consume(tile_id, 2, b1);
+            consume(tile_id, 4, b0);
         }
         __syncthreads();
 
@@ -259,9 +289,13 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 f32x4 o = acc[y % KS];
                 acc[y % KS] = z;
                 const int gy = gy0 + y;
+                if (t == 1) {
+                    // tokens outside the image contribute nothing: their aggregated K is made 0, which
+                    // also removes their V from the state; Q rows of such tokens are simply not stored
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;      // tokens outside the image contribute nothing
+                    for (int i = 0; i < 4; ++i)
+                        if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;
+                }
                 if (t == 2) {
                     // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
                     f32x4 vf;
@@ -289,8 +323,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                     if (t == 1) {
                         f32x4 kf = Tr::mma16(z, dwf, gpw_k);
                         if constexpr (Tr::kHiLo) kf = Tr::mma16(kf, dwf_lo, gpw_k);
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) kf[c] = fmaxf(kf[c], 0.f);      // Eq. (2): relu(K)
+                        kf = relu_bits_f32(kf);       // Eq. (2): relu(K), one integer max per value
                         ks_agg += (kf[0] + kf[1]) + (kf[2] + kf[3]);
                         if constexpr (Tr::kHiLo) frag_split<T>(kf, aggK[y], aggK_lo[y]);
                         else aggK[y] = frag_from_f32<T>(kf);
@@ -312,8 +345,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // ---------------- workgroup partial state
     ks_agg += __shfl_xor(ks_agg, 16);
     ks_agg += __shfl_xor(ks_agg, 32);
-    ks_raw += __shfl_xor(ks_raw, 16);
-    ks_raw += __shfl_xor(ks_raw, 32);
     __syncthreads();   // tile memory is dead from here on
     // per wave: [which][lane] accumulator quads, then [which][16] Ksum; which 0 = aggregated (V before
     // its grouped 1x1), 1 = raw
@@ -323,10 +354,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         float* mine = red + wave * kWaveFloats;
         *(f32x4*)(mine + lane * 4) = kv_agg;
         *(f32x4*)(mine + 256 + lane * 4) = kv_raw;
-        if (q == 0) {
-            mine[512 + x16] = ks_agg;
-            mine[512 + 16 + x16] = ks_raw;
-        }
+        if (q == 0) mine[512 + x16] = ks_agg;
+        if (x16 == 0) *(f32x4*)(mine + 512 + 16 + q * 4) = ks_raw4;
     }
     __syncthreads();
     {

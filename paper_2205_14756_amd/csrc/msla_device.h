@@ -140,6 +140,32 @@ __device__ __forceinline__ typename Traits<T>::Frag frag_relu(typename Traits<T>
     return f;
 }
 
+// The same rectifier as integer maxima on the bit patterns (negative values and -0 have the sign
+// bit set, so they compare below +0 as integers): one instruction per pair of 16-bit values,
+// no canonicalisation of the input.  NaNs with a clear sign bit pass through.
+// (Whole vectors are bit-cast here: __builtin_bit_cast applied to a single vector ELEMENT reads
+// element 0 with this compiler.)
+template <class T>
+__device__ __forceinline__ typename Traits<T>::Frag frag_relu_bits(typename Traits<T>::Frag f) {
+    if constexpr (sizeof(T) == 2) {
+        typedef short i16x4v __attribute__((ext_vector_type(4)));
+        const i16x4v zero = {0, 0, 0, 0};
+        return __builtin_bit_cast(typename Traits<T>::Frag,
+                                  __builtin_elementwise_max(__builtin_bit_cast(i16x4v, f), zero));
+    } else {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        const i32x4 zero = {0, 0, 0, 0};
+        return __builtin_bit_cast(typename Traits<T>::Frag,
+                                  __builtin_elementwise_max(__builtin_bit_cast(i32x4, f), zero));
+    }
+}
+
+__device__ __forceinline__ f32x4 relu_bits_f32(f32x4 v) {
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const i32x4 zero = {0, 0, 0, 0};
+    return __builtin_bit_cast(f32x4, __builtin_elementwise_max(__builtin_bit_cast(i32x4, v), zero));
+}
+
 // 4 consecutive elements (one Frag) to / from memory.  8 bytes for the 16-bit
 // types, 16 bytes for fp32; the address must be aligned to 8 bytes (LDS tiles
 // are padded to 8-byte pixel strides), so fp32 moves as two 8-byte halves.
