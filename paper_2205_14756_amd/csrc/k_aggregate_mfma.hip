@@ -18,7 +18,9 @@
 // A wave sweeps a 16-token-wide strip downwards: each input row is read once
 // from LDS and multiplied into the (up to) k rolling accumulators of the
 // output rows it touches.  The Toeplitz operands of a head's 48 channels are
-// built once per workgroup and stay in registers.
+// built once per workgroup and stay in registers.  The workgroup is a two-stage pipeline: four waves
+// stage the next tile (global loads, transposition, raw branch) while four waves sweep the current
+// one (a 16-column strip x 8 rows each), so HBM latency and matrix-core work overlap inside a CU.
 //
 // The halo tile is kept channel-planar in LDS ([channel][row][x], x contiguous),
 // which is what B_b wants; the global maps are token-major, so staging goes
@@ -41,7 +43,9 @@ namespace {
 
 constexpr int MTH = kAggMfmaTileH;   // 16 tile rows: two halves of 8, one per wave pair
 constexpr int MTW = kAggMfmaTileW;   // 32 tile columns: two 16-token strips
-constexpr int kThreads = 256;
+constexpr int kSweepWaves = 4;       // 4 or 8: each sweeps a 16-column strip x 8 or 4 rows
+constexpr int kThreads = (4 + kSweepWaves) * 64;     // 4 staging waves + the sweeping waves
+constexpr int kSweepRows = MTH / (kSweepWaves / 2);
 
 template <int KS>
 struct MLds {
@@ -55,7 +59,7 @@ struct MLds {
     static constexpr int kPlanarBytes = 48 * kChanBytes;
     static constexpr int kTokStride = 80;                      // transposition buffer: 16 tokens x 16 fp32 (+pad)
     static constexpr int kTransBytes = 16 * kTokStride;
-    static constexpr int kBytes = kPlanarBytes + 4 * kTransBytes;
+    static constexpr int kBytes = 2 * kPlanarBytes + kSweepWaves * kTransBytes;   // two tiles in flight
     static_assert(LW <= 36 && (kChanBytes / 4) % 32 == 8, "LDS layout");
 };
 
@@ -89,7 +93,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     constexpr int P = L::P;
     constexpr int NS = 2;                 // k-steps of 4 input columns: 4 + 2P <= 8
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* planar = lds;
     float* red = (float*)lds;             // reused after the last tile
 
     const unsigned Lid = xcd_remap(blockIdx.x, gridDim.x);
@@ -102,14 +105,25 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: row/strip math stays on the SALU
+    const int role = wave >= 4;           // waves 0-3 stage tile i+1 while the others sweep tile i
+    const int w4 = wave & 3;              // staging wave index
+    const int sw = (wave - 4) & (kSweepWaves - 1);   // sweeping wave index
     const int x16 = lane & 15, q = lane >> 4;      // 16x16 MFMA view of the lane
     const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block (channel), row/column inside it
-    char* trans = lds + L::kPlanarBytes + wave * L::kTransBytes;
+    char* trans = lds + 2 * L::kPlanarBytes + sw * L::kTransBytes;
 
     const T* wdw = (const T*)a.w_dw + (long)h * 48 * KS * KS;
     const T* wgp = (const T*)a.w_gpw + (long)h * 48 * 16;
 
-    // Toeplitz operands of the three 16-channel groups: lane (channel blk, output i = sub)
+    // Toeplitz operands of the three 16-channel groups: lane (channel blk, output i = sub).  The head's
+    // 48 x KS x KS filter taps are fetched once, coalesced, into LDS (the tile area is still free);
+    // each lane then picks its band entries with branch-free LDS reads (index clamped, value masked).
+    {
+        T* wl = (T*)lds;
+        for (int i = threadIdx.x; i < 48 * KS * KS; i += kThreads) wl[i] = wdw[i];
+        if (threadIdx.x == 0) wl[48 * KS * KS] = Tr::from_f32(0.f);     // the entry read by masked-out slots
+    }
+    __syncthreads();
     Frag toep[3][KS][NS];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
@@ -120,10 +134,10 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int v = 4 * s + k - sub;
-                    T val = Tr::from_f32(0.f);
-                    if (v >= 0 && v < KS) val = wdw[((t * 16 + blk) * KS + u) * KS + v];
-                    toep[t][u][s][k] = val;
+                    const int idx = (v >= 0 && v < KS) ? ((t * 16 + blk) * KS + u) * KS + v : 48 * KS * KS;
+                    toep[t][u][s][k] = ((const T*)lds)[idx];
                 }
+    __syncthreads();   // the tap table sits where the first tile will be staged
     // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
     const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
     const Frag gpw_k = load_frag<T>(wgp + (1 * 16 + x16) * 16 + q * 4);
@@ -159,7 +173,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const int tile_begin = chunk * a.tiles_per_chunk;
     const int tile_end = min(n_tiles, tile_begin + a.tiles_per_chunk);
 
-    const int strip = wave & 1, half = wave >> 1;
+    const int strip = sw & 1, part = sw >> 1;     // 16-column strip, group of kSweepRows rows
     // lane part of the staging load addresses: token x16 of a 16-column group, channels of q
     const long lane_q_off = (long)x16 * a.q_ts + q * 4;
     const long lane_k_off = (long)x16 * a.k_ts + q * 8;
@@ -177,11 +191,11 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     constexpr int kBatches = ((L::LH + 3) / 4 + 1) / 2;
     static_assert(kBatches == 3, "staging schedule below assumes 3 batches per tile");
 
-    auto issue = [&](int tile_id, int it, Batch& bt) {
+    auto issue = [&](int tile_id, int it, Batch& bt) {   // staging waves
         const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
-            const int ly = wave + 4 * (it + rr);
+            const int ly = w4 + 4 * (it + rr);
             const int gy = ty0 - P + ly;
             const bool row_ok = ly < L::LH && gy >= 0 && gy < a.H;
             // wave-uniform row bases; the lane part of the address is loop-invariant
@@ -202,11 +216,11 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         }
     };
 
-    auto consume = [&](int tile_id, int it, const Batch& bt) {
+    auto consume = [&](int tile_id, int it, const Batch& bt, char* planar) {
         const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
-            const int ly = wave + 4 * (it + rr);
+            const int ly = w4 + 4 * (it + rr);
             if (ly >= L::LH) break;
             const int gy = ty0 - P + ly;
             const bool row_interior = ly >= P && ly < P + MTH;
@@ -245,40 +259,63 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         }
     };
 
-    for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
-        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
-        {
-            Batch b0, b1;
-            issue(tile_id, 0, b0);
-            issue(tile_id, 2, b1);
-            __syncthreads();   // previous tile fully consumed
-            consume(tile_id, 0, b0);
-            issue(tile_id, 4, b0);
-            consume(tile_id, 2, b1);
-            consume(tile_id, 4, b0);
+    // Software pipeline over the workgroup's tiles with two LDS tile buffers: in step i the staging
+    // waves fill buffer (i+1)&1 with tile i+1 while the sweeping waves work through tile i in buffer
+    // i&1; one barrier per step hands the buffers over.  A staging wave keeps a ring of three load
+    // batches: as soon as a batch is consumed, the same rows of the NEXT tile are requested into its
+    // registers, so two to three batches per wave are in flight all the time and the HBM latency is
+    // covered by the rest of the step (the barrier gates the LDS writes, not the loads).
+    // The two roles run separate loops with the same number of barriers (n_my_tiles + 1), so that
+    // the register allocator does not have to keep one role's state alive for the other.
+    const int n_my_tiles = tile_end - tile_begin;
+    if (role == 0) {
+        Batch ring0, ring1, ring2;
+        if (n_my_tiles > 0) {
+            issue(tile_begin, 0, ring0);
+            issue(tile_begin, 2, ring1);
+            issue(tile_begin, 4, ring2);
         }
-        __syncthreads();
-
-        // ---------------- depthwise sweep: this wave's strip (16 columns) x half (8 rows)
+        for (int step = -1; step < n_my_tiles; ++step) {
+            if (step + 1 < n_my_tiles) {
+                const int tile_id = tile_begin + step + 1;
+                const bool more = step + 2 < n_my_tiles;
+                char* planar = lds + ((step + 1) & 1) * L::kPlanarBytes;
+                consume(tile_id, 0, ring0, planar);
+                if (more) issue(tile_id + 1, 0, ring0);
+                consume(tile_id, 2, ring1, planar);
+                if (more) issue(tile_id + 1, 2, ring1);
+                consume(tile_id, 4, ring2, planar);
+                if (more) issue(tile_id + 1, 4, ring2);
+            }
+            __syncthreads();
+        }
+    } else {
+    for (int step = -1; step < n_my_tiles; ++step) {
+        if (step >= 0) {
+        const int tile_id = tile_begin + step;
+        const char* planar = lds + (step & 1) * L::kPlanarBytes;
+        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+        // ---------------- depthwise sweep: this wave's strip (16 columns) x part (kSweepRows rows)
+        constexpr int R = kSweepRows;
         const int col0 = 16 * strip + 4 * sub;            // interior column of this lane's x-block
-        const int gy0 = ty0 + 8 * half;
+        const int gy0 = ty0 + R * part;
         const int gx0 = tx0 + col0;
-        Frag aggK[8], aggK_lo[8];
+        Frag aggK[R], aggK_lo[R];
 #pragma unroll
         for (int pass = 0; pass < 3; ++pass) {
             const int t = (pass == 0) ? 1 : (pass == 1) ? 2 : 0;     // K, V, Q
-            const char* src = planar + (t * 16 + blk) * L::kChanBytes + (8 * half) * L::kRowBytes + col0 * 2;
+            const char* src = planar + (t * 16 + blk) * L::kChanBytes + (R * part) * L::kRowBytes + col0 * 2;
             f32x4 acc[KS];
 #pragma unroll
             for (int i = 0; i < KS; ++i) acc[i] = z;
 #pragma unroll
-            for (int r = 0; r < 8 + 2 * P; ++r) {
+            for (int r = 0; r < R + 2 * P; ++r) {
                 const Frag d0 = load_frag<T>(src + r * L::kRowBytes);
                 const Frag d1 = load_frag<T>(src + r * L::kRowBytes + 8);
 #pragma unroll
                 for (int u = 0; u < KS; ++u) {
                     const int y = r - u;
-                    if (y < 0 || y >= 8) continue;
+                    if (y < 0 || y >= R) continue;
                     acc[y % KS] = M4<T>::mma(toep[t][u][0], d0, acc[y % KS]);
                     acc[y % KS] = M4<T>::mma(toep[t][u][1], d1, acc[y % KS]);
                 }
@@ -340,6 +377,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 }
             }
         }
+        }
+        __syncthreads();
+    }
     }
 
     // ---------------- workgroup partial state
@@ -349,7 +389,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // per wave: [which][lane] accumulator quads, then [which][16] Ksum; which 0 = aggregated (V before
     // its grouped 1x1), 1 = raw
     constexpr int kWaveFloats = 2 * 256 + 2 * 16;
-    float* msum = red + 4 * kWaveFloats;          // [16][16] summed pre-1x1 state of the aggregated branch
+    constexpr int kWaves = kThreads / 64;         // staging waves hold the raw state, sweeping waves the aggregated
+    float* msum = red + kWaves * kWaveFloats;          // [16][16] summed pre-1x1 state of the aggregated branch
     {
         float* mine = red + wave * kWaveFloats;
         *(f32x4*)(mine + lane * 4) = kv_agg;
@@ -358,12 +399,17 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         if (x16 == 0) *(f32x4*)(mine + 512 + 16 + q * 4) = ks_raw4;
     }
     __syncthreads();
-    {
+    auto wave_sum = [&](int src) {      // fixed order
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) t += red[w * kWaveFloats + src];
+        return t;
+    };
+    if (threadIdx.x < 256) {
         // M[e][c] of the aggregated branch, summed over the waves: lane (c, e / 4), element e % 4
         const int j = threadIdx.x;
         const int e = j >> 4, c = j & 15;
-        const int src = ((e >> 2) * 16 + c) * 4 + (e & 3);
-        msum[j] = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+        msum[j] = wave_sum(((e >> 2) * 16 + c) * 4 + (e & 3));
     }
     __syncthreads();
     for (int j = threadIdx.x; j < 2 * kStateSize; j += kThreads) {
@@ -372,11 +418,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         const int e = idx / 17, f = idx - e * 17;
         float s;
         if (f == 16) {
-            const int src = 512 + which * 16 + e;
-            s = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+            s = wave_sum(512 + which * 16 + e);
         } else if (which == 1) {
-            const int src = 256 + ((e >> 2) * 16 + f) * 4 + (e & 3);
-            s = (red[src] + red[kWaveFloats + src]) + (red[2 * kWaveFloats + src] + red[3 * kWaveFloats + src]);
+            s = wave_sum(256 + ((e >> 2) * 16 + f) * 4 + (e & 3));
         } else {
             // the grouped 1x1 of V, applied to the summed state: KV[e][f] = sum_c M[e][c] w_gpw[f][c]
             const T* wv = wgp + (2 * 16 + f) * 16;

@@ -57,7 +57,7 @@ msla_status check_shape(int B, int H, int W, int heads, int head_dim, const int*
     } else if (n_scales > 0) {
         tiles = (long)((H + msla::kAggMfmaTileH - 1) / msla::kAggMfmaTileH) *
                 ((W + msla::kAggMfmaTileW - 1) / msla::kAggMfmaTileW);
-        target_blocks = 512;   // two resident workgroups per CU; each builds its operands once
+        target_blocks = 256;   // one pipelined 8-wave workgroup per CU; each builds its operands once
     } else {
         tiles = (N + 63) / 64;
     }
