@@ -47,6 +47,22 @@ struct GemmTile {
         }
     }
 
+    // Same, with the matrix rows given by a map (a permuted order of the weight rows).
+    template <int NV, class RowMap>
+    static __device__ __forceinline__ void load_global_rows(u32x4 (&regs)[NV], const T* __restrict__ base,
+                                                            int row0, int row_limit, long ld, int k0,
+                                                            int k_limit, const RowMap& row_of) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int v = threadIdx.x + i * kThreads;
+            const int row = row0 + (v >> 3);
+            const int k = k0 + (v & 7) * Tr::kVec;
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (row < row_limit && k < k_limit) val = *(const u32x4*)(base + (long)row_of(row) * ld + k);
+            regs[i] = val;
+        }
+    }
+
     template <int NV>
     static __device__ __forceinline__ void store_lds(char* lds, const u32x4 (&regs)[NV]) {
 #pragma unroll
@@ -60,10 +76,6 @@ struct GemmTile {
     static __device__ __forceinline__ void mma(f32x4 (&acc)[4][4], const char* ldsR, const char* ldsC,
                                                int wr, int wc) {
         const int x = lane_id() & 15, q = lane_id() >> 4;
-#ifdef MSLA_EXP_NOMMA
-        if (ldsR[0] == 77 && ldsC[1] == 78) acc[0][0][0] += 1.f;
-        return;
-#endif
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             Vec a[4], b[4];
@@ -102,11 +114,47 @@ struct GemmTile {
 #pragma unroll
             for (int io = 0; io < 4; ++io) {
                 const int oc = oc0 + wr * 64 + io * 16 + q * 4;
-#ifdef MSLA_EXP_NOSTORE
-                if (oc < oc_limit && acc[io][jt][0] == 12345.678f) ep(tok, oc, acc[io][jt]);
-#else
                 if (oc < oc_limit) ep(tok, oc, acc[io][jt]);
-#endif
+            }
+        }
+    }
+
+    // Epilogue through LDS: a wave parks one 16-token x 64-channel piece of its results at a time in
+    // its own staging rows and writes it out as 16-byte words, so that consecutive lanes cover whole
+    // 128-byte runs of a token's channels (an 8-byte-per-lane scatter costs the address path one
+    // cycle per 32-byte segment).  dest(token, channel) returns where 16 bytes of channels starting
+    // at a multiple of 16/sizeof(T) go; it is only called for valid tokens and channels.
+    static constexpr int kStageRow = 64 * (int)sizeof(T) + 16;
+    static constexpr int kStageWave = 16 * kStageRow;
+    static constexpr int kStageBytes = WR * WC * kStageWave;
+
+    template <class Dest>
+    static __device__ __forceinline__ void epilogue_lds(const f32x4 (&acc)[4][4], char* stage, long tok0,
+                                                        long tok_limit, int oc0, int oc_limit, int wr, int wc,
+                                                        const Dest& dest) {
+        const int lane = lane_id();
+        const int x = lane & 15, q = lane >> 4;
+        char* mine = stage + (wr + WR * wc) * kStageWave;
+        constexpr int kVecPerRow = 64 * (int)sizeof(T) / 16;        // 8 (16-bit) or 16 (fp32)
+        constexpr int kPer = 16 * kVecPerRow / 64;                  // vectors per lane per piece
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int io = 0; io < 4; ++io)
+                store_frag<T>(mine + x * kStageRow + (io * 16 + q * 4) * (int)sizeof(T), frag_from_f32<T>(acc[io][jt]));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int v = lane + 64 * i;
+                const int row = v / kVecPerRow, cv = v % kVecPerRow;
+                const long tok = tok0 + wc * 64 + jt * 16 + row;
+                const int oc = oc0 + wr * 64 + cv * Tr::kVec;
+                const u32x4 val = *(const u32x4*)(mine + row * kStageRow + cv * 16);
+                if (tok < tok_limit && oc < oc_limit) *(u32x4*)dest(tok, oc) = val;
             }
         }
     }

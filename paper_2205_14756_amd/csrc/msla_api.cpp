@@ -137,6 +137,20 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
 
 }  // namespace
 
+namespace msla {
+int compute_units() {
+    static int cached = 0;      // a device property, not call state; benign if two threads race to set it
+    if (cached <= 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;            // MI355X
+        cached = n;
+    }
+    return cached;
+}
+}  // namespace msla
+
 extern "C" {
 
 const char* msla_error_string(msla_status status) {

@@ -59,6 +59,9 @@ hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, co
                                 const void* w_proj, void* out, long n_tokens, int tokens_per_image,
                                 int n_hb, int c_out, float eps, hipStream_t stream);
 
+// Number of compute units of the current device (queried once per process).
+int compute_units();
+
 constexpr int kAggTileH = 8;        // vector-ALU kernel (fp32 storage)
 constexpr int kAggTileW = 32;
 constexpr int kAggMfmaTileH = 16;   // matrix-core kernel (fp16 / bf16 storage)
