@@ -8,8 +8,11 @@
 // operand", so a lane ends up with 4 consecutive output channels of one token
 // and stores them as one 8- or 16-byte word.
 //
-// LDS rows hold 128 contraction bytes and are padded to 144 so that 8 lanes
-// reading the same 16-byte column of 8 consecutive rows touch all 32 banks.
+// LDS layout of a 128-byte contraction slab of R rows: row-major with a row pitch of 160 bytes.
+// With that pitch both access patterns run at the full LDS rate: an MFMA operand read (16 lanes =
+// 16 consecutive rows of one 16-byte column, four columns per instruction) and the copy of rows
+// from HBM (8 lanes per row).  A pitch of 144 bytes, or column planes padded by 16 bytes, halve
+// the 16-byte read rate on this chip.
 #pragma once
 #include "msla_device.h"
 
@@ -23,9 +26,9 @@ struct GemmTile {
     static constexpr int BR = WR * 64;                 // weight rows (output channels) per tile
     static constexpr int BC = WC * 64;                 // tokens per tile
     static constexpr int BK = 128 / (int)sizeof(T);    // contraction elements per iteration
-    static constexpr int kRowStride = 144;             // bytes
-    static constexpr int kLdsR = BR * kRowStride;
-    static constexpr int kLdsC = BC * kRowStride;
+    static constexpr int kRow = 160;                   // LDS row pitch in bytes
+    static constexpr int kLdsR = BR * kRow;
+    static constexpr int kLdsC = BC * kRow;
     static constexpr int kVecR = BR * 8 / kThreads;    // 16-byte vectors per thread, weight tile
     static constexpr int kVecC = BC * 8 / kThreads;    // ... token tile
     static_assert(BR * 8 % kThreads == 0 && BC * 8 % kThreads == 0, "tile/thread mismatch");
@@ -63,35 +66,50 @@ struct GemmTile {
         }
     }
 
+    // i-th 16-byte vector of this thread's share of a slab -> LDS
+    static __device__ __forceinline__ void store_lds_one(char* lds, u32x4 reg, int i) {
+        const int v = threadIdx.x + i * kThreads;
+        *(u32x4*)(lds + (v >> 3) * kRow + (v & 7) * 16) = reg;
+    }
     template <int NV>
     static __device__ __forceinline__ void store_lds(char* lds, const u32x4 (&regs)[NV]) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int v = threadIdx.x + i * kThreads;
-            *(u32x4*)(lds + (v >> 3) * kRowStride + (v & 7) * 16) = regs[i];
-        }
+        for (int i = 0; i < NV; ++i) store_lds_one(lds, regs[i], i);
+    }
+    static __device__ __forceinline__ void store_lds_r(char* lds, const u32x4 (&regs)[kVecR]) { store_lds(lds, regs); }
+    static __device__ __forceinline__ void store_lds_c(char* lds, const u32x4 (&regs)[kVecC]) { store_lds(lds, regs); }
+
+    // One MFMA operand: 16 rows starting at row0 of the tile, contraction half kk (0 or 1).
+    static __device__ __forceinline__ Vec load_frag_lds(const char* lds, int row0, int kk) {
+        const int x = lane_id() & 15, q = lane_id() >> 4;
+        return __builtin_bit_cast(Vec, *(const u32x4*)(lds + (row0 + x) * kRow + (kk * 4 + q) * 16));
+    }
+    // acc[io][jt] += W-tile(rows wr*64 + io*16 ..) . X-tile(rows wc*64 + jt*16 ..)^T
+    static __device__ __forceinline__ void load_frags(Vec (&a)[4], Vec (&b)[4], const char* ldsR, const char* ldsC,
+                                                      int wr, int wc, int kk) {
+#pragma unroll
+        for (int io = 0; io < 4; ++io) a[io] = load_frag_lds(ldsR, wr * 64 + io * 16, kk);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) b[jt] = load_frag_lds(ldsC, wc * 64 + jt * 16, kk);
     }
 
-    // acc[io][jt] += W-tile(rows wr*64 + io*16 ..) . X-tile(rows wc*64 + jt*16 ..)^T
+    struct Frags {
+        Vec a[4], b[4];
+    };
+    static __device__ __forceinline__ void mma_half(f32x4 (&acc)[4][4], const Frags& f) {
+#pragma unroll
+        for (int io = 0; io < 4; ++io)
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], f.a[io], f.b[jt]);
+    }
+
     static __device__ __forceinline__ void mma(f32x4 (&acc)[4][4], const char* ldsR, const char* ldsC,
                                                int wr, int wc) {
-        const int x = lane_id() & 15, q = lane_id() >> 4;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            Vec a[4], b[4];
-#pragma unroll
-            for (int io = 0; io < 4; ++io)
-                a[io] = __builtin_bit_cast(Vec, *(const u32x4*)(ldsR + (wr * 64 + io * 16 + x) * kRowStride +
-                                                                 (kk * 4 + q) * 16));
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt)
-                b[jt] = __builtin_bit_cast(Vec, *(const u32x4*)(ldsC + (wc * 64 + jt * 16 + x) * kRowStride +
-                                                                 (kk * 4 + q) * 16));
-#pragma unroll
-            for (int io = 0; io < 4; ++io)
-#pragma unroll
-                for (int jt = 0; jt < 4; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], a[io], b[jt]);
-        }
+        Frags f0, f1;
+        load_frags(f0.a, f0.b, ldsR, ldsC, wr, wc, 0);
+        load_frags(f1.a, f1.b, ldsR, ldsC, wr, wc, 1);
+        mma_half(acc, f0);
+        mma_half(acc, f1);
     }
 
     static __device__ __forceinline__ void zero(f32x4 (&acc)[4][4]) {
@@ -128,10 +146,11 @@ struct GemmTile {
     static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kStageBytes = WR * WC * kStageWave;
 
-    template <class Dest>
-    static __device__ __forceinline__ void epilogue_lds(const f32x4 (&acc)[4][4], char* stage, long tok0,
-                                                        long tok_limit, int oc0, int oc_limit, int wr, int wc,
-                                                        const Dest& dest) {
+    // out.store(first channel of the wave's 64-channel piece (wave-uniform), token row within the
+    // tile, channel, 16 bytes) writes -- or drops, beyond the ragged ends -- one word.
+    template <class TileOut>
+    static __device__ __forceinline__ void epilogue_lds(const f32x4 (&acc)[4][4], char* stage, int oc0, int wr,
+                                                        int wc, const TileOut& out) {
         const int lane = lane_id();
         const int x = lane & 15, q = lane >> 4;
         char* mine = stage + (wr + WR * wc) * kStageWave;
@@ -151,10 +170,8 @@ struct GemmTile {
             for (int i = 0; i < kPer; ++i) {
                 const int v = lane + 64 * i;
                 const int row = v / kVecPerRow, cv = v % kVecPerRow;
-                const long tok = tok0 + wc * 64 + jt * 16 + row;
-                const int oc = oc0 + wr * 64 + cv * Tr::kVec;
                 const u32x4 val = *(const u32x4*)(mine + row * kStageRow + cv * 16);
-                if (tok < tok_limit && oc < oc_limit) *(u32x4*)dest(tok, oc) = val;
+                out.store(oc0 + wr * 64, wc * 64 + jt * 16 + row, oc0 + wr * 64 + cv * Tr::kVec, val);
             }
         }
     }

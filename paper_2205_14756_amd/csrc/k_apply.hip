@@ -138,7 +138,7 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
             qreg[g][j] = (ok[g] && j < n_hb) ? load_frag<T>(q_row[g] + j * 16) : frag_zero<T>();
 
     for (int k0 = 0; k0 < K; k0 += G::BK) {
-        G::store_lds(ldsR, rw);
+        G::store_lds_r(ldsR, rw);
         const int m0 = k0 >> 4;
 #pragma unroll
         for (int j = 0; j < HB; ++j) {
@@ -149,7 +149,8 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
             for (int g = 0; g < TG; ++g) {
                 f32x4 o = {0.f, 0.f, 0.f, 0.f};
                 if (live) o = att_unit<T>(qreg[g][j], state, eps_s);
-                const int off = ((g * kWaves + wave) * 16 + x16) * G::kRowStride + (j * 16 + q * 4) * (int)sizeof(T);
+                const int colb = (j * 16 + q * 4) * (int)sizeof(T);      // byte column inside the 128-byte slab
+                const int off = ((g * kWaves + wave) * 16 + x16) * G::kRow + colb;
                 if constexpr (kHiLo) {
                     Frag hi, lo;
                     frag_split<T>(o, hi, lo);

@@ -191,6 +191,24 @@ __device__ __forceinline__ void store_frag(void* p, typename Traits<T>::Frag f) 
     }
 }
 
+// Raw buffer resources: loads and stores through one are range-checked by the hardware against
+// the byte count (a load out of range returns zero, a store out of range is dropped), which
+// replaces per-lane branches at ragged ends.  Offsets are 32-bit, so a resource spans at most
+// 2^31 - 1 bytes from its base; kOobOffset lies beyond any such span.
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+constexpr unsigned kOobOffset = 0x80000000u;
+__device__ __forceinline__ BufRsrc make_rsrc(const void* base, long bytes) {
+    const int n = bytes > 0x7fffffffL ? 0x7fffffff : (bytes < 0 ? 0 : (int)bytes);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(BufRsrc r, unsigned voffset, int soffset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voffset, soffset, 0);
+}
+__device__ __forceinline__ void buf_store16(BufRsrc r, unsigned voffset, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, 0, 0);
+}
+
+
 // Workgroup id -> logical id so that consecutive logical ids run on the same
 // XCD.  The hardware deals workgroups round-robin over the 8 XCDs (each with
 // its own L2); neighbours in the logical order share cache lines, so they
