@@ -146,8 +146,8 @@ struct GemmTile {
     static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kStageBytes = WR * WC * kStageWave;
 
-    // out.store(first channel of the wave's 64-channel piece (wave-uniform), token row within the
-    // tile, channel, 16 bytes) writes -- or drops, beyond the ragged ends -- one word.
+    // out.store(first and past-the-end channel of the wave's 64-channel piece (wave-uniform), token
+    // row within the tile, channel, 16 bytes) writes -- or drops, beyond the ragged ends -- one word.
     template <class TileOut>
     static __device__ __forceinline__ void epilogue_lds(const f32x4 (&acc)[4][4], char* stage, int oc0, int wr,
                                                         int wc, const TileOut& out) {
@@ -171,7 +171,7 @@ struct GemmTile {
                 const int v = lane + 64 * i;
                 const int row = v / kVecPerRow, cv = v % kVecPerRow;
                 const u32x4 val = *(const u32x4*)(mine + row * kStageRow + cv * 16);
-                out.store(oc0 + wr * 64, wc * 64 + jt * 16 + row, oc0 + wr * 64 + cv * Tr::kVec, val);
+                out.store(oc0 + wr * 64, oc0 + wr * 64 + 64, wc * 64 + jt * 16 + row, oc0 + wr * 64 + cv * Tr::kVec, val);
             }
         }
     }

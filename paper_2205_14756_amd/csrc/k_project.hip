@@ -9,6 +9,10 @@
 #define MSLA_PROJ_WC 2
 #endif
 
+#ifndef MSLA_PROJ_BARRIER_AT
+#define MSLA_PROJ_BARRIER_AT 0
+#endif
+
 namespace msla {
 namespace {
 
@@ -27,7 +31,7 @@ struct PlainDest {
         BufRsrc y;
         unsigned row_bytes;
         int c_out;
-        __device__ __forceinline__ void store(int, int row, int oc, u32x4 v) const {
+        __device__ __forceinline__ void store(int, int, int row, int oc, u32x4 v) const {
             buf_store16(y, oc < c_out ? row * row_bytes + oc * (unsigned)sizeof(T) : kOobOffset, v);
         }
     };
@@ -54,10 +58,10 @@ struct QkvSplitDest {
         BufRsrc q, kv;
         unsigned q_row_bytes, kv_row_bytes;
         int Ct;
-        __device__ __forceinline__ void store(int piece0, int row, int vc, u32x4 v) const {
+        __device__ __forceinline__ void store(int piece0, int piece_end, int row, int vc, u32x4 v) const {
             constexpr unsigned sz = (unsigned)sizeof(T);
             if (piece0 < Ct) buf_store16(q, vc < Ct ? row * q_row_bytes + vc * sz : kOobOffset, v);
-            if (piece0 + 64 > Ct)
+            if (piece_end > Ct)
                 buf_store16(kv, (vc >= Ct && vc < 3 * Ct) ? row * kv_row_bytes + (vc - Ct) * sz : kOobOffset, v);
         }
     };
@@ -183,12 +187,13 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
             __builtin_amdgcn_sched_barrier(0);
         }
         fetch_end();
-        __syncthreads();
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
+            if (m == MSLA_PROJ_BARRIER_AT) __syncthreads();
             acc[m >> 2][m & 3] = Traits<T>::mma_vec(acc[m >> 2][m & 3], f1.a[m >> 2], f1.b[m & 3]);
-            if (m < 4) f0.a[m] = G::load_frag_lds(next, wr * 64 + m * 16, 0);
-            else if (m < 8) f0.b[m - 4] = G::load_frag_lds(next + G::kLdsR, wc * 64 + (m - 4) * 16, 0);
+            constexpr int r0 = MSLA_PROJ_BARRIER_AT;
+            if (m >= r0 && m < r0 + 4) f0.a[m - r0] = G::load_frag_lds(next, wr * 64 + (m - r0) * 16, 0);
+            else if (m >= r0 + 4 && m < r0 + 8) f0.b[m - r0 - 4] = G::load_frag_lds(next + G::kLdsR, wc * 64 + (m - r0 - 4) * 16, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         cur ^= 1;
@@ -225,6 +230,193 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
     }
 }
 
+// ---------------------------------------------------------------- weight-stationary form
+// When a weight row is at most 512 bytes (the contraction is short, as in this module's 1x1
+// projections), a wave keeps its 48 output channels' weights in registers for the whole kernel --
+// KCH operand fragments per 16 channels -- and only the tokens stream: a workgroup of 4 waves owns
+// 192 channels and walks over token tiles of 32.  A tile is copied HBM -> registers -> LDS once
+// (double-buffered, one barrier per tile) and every wave reads all of it as MFMA operands.
+// Against the tiled form above this moves a fraction of the bytes through LDS and L2 per
+// multiply-add and needs no weight traffic in the loop at all.  Two such workgroups share a CU
+// (one wave of each per SIMD); they drift apart, so one's barrier and result stores are covered
+// by the other's matrix instructions.
+template <class T, int KCH>
+struct WsShape {
+    static_assert(sizeof(T) == 2 && KCH % 2 == 0, "16-bit elements, whole 128-byte slabs");
+    static constexpr int kWaves = 4, kThreads = 256, kResident = 2;
+    static constexpr int IO = 3;                         // 16-channel groups per wave
+    static constexpr int JT = 2;                         // 16-token groups per tile
+    static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
+    static constexpr int TB = JT * 16;                   // tokens per tile
+    static constexpr int NS = KCH / 2;                   // 128-byte slabs per token row
+    static constexpr int kRow = 160;                     // LDS row pitch of a slab (full-rate reads and writes)
+    static constexpr int kSlab = TB * kRow;
+    static constexpr int kBuf = NS * kSlab;
+    static constexpr int kStageRow = kChanWave * 2 + 16;
+    static constexpr int kStageWave = 16 * kStageRow;
+    static constexpr int kWeightStage = kChanBlock * kRow;        // one slab of the workgroup's weight rows
+    static constexpr int kLds = (2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage) + kWaves * kStageWave;
+    static_assert(TB * 8 == kThreads, "one 16-byte vector per thread and slab");
+};
+
+template <class T, int KCH, class Epilogue>
+__global__ __launch_bounds__(256) void project_ws_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                         long n_tokens, int c_in, int c_out, int n_cg,
+                                                         long n_tt, long tiles_per_block, Epilogue ep) {
+    typedef WsShape<T, KCH> S;
+    typedef typename Traits<T>::Vec Vec;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const unsigned L = xcd_remap(blockIdx.x, gridDim.x);
+    const int cg = (int)(L % (unsigned)n_cg);
+    const long t_begin = (long)(L / (unsigned)n_cg) * tiles_per_block;
+    const long t_end = t_begin + tiles_per_block < n_tt ? t_begin + tiles_per_block : n_tt;
+    if (t_begin >= t_end) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = lane_id(), x16 = lane & 15, q = lane >> 4;
+    const unsigned row_bytes = (unsigned)c_in * 2u;
+    const int ch0 = cg * S::kChanBlock + wave * S::kChanWave;     // this wave's first channel
+
+    // token tile copy: thread = (row tid/8, 16-byte chunk tid%8) of each of the NS slabs
+    const unsigned g_off = (threadIdx.x >> 3) * row_bytes + (threadIdx.x & 7) * 16;
+    const unsigned l_off = (threadIdx.x >> 3) * S::kRow + (threadIdx.x & 7) * 16;
+    u32x4 regs[S::NS];
+    auto fetch = [&](long tile) {
+        const long tok0 = tile * S::TB;
+        const BufRsrc xres = make_rsrc(x + tok0 * c_in, tile < t_end ? (n_tokens - tok0) * (long)row_bytes : 0);
+#pragma unroll
+        for (int i = 0; i < S::NS; ++i)
+            regs[i] = buf_load16(xres, (i * 128 + (threadIdx.x & 7) * 16 < row_bytes) ? g_off + i * 128 : kOobOffset, 0);
+    };
+    auto park = [&](char* buf) {
+#pragma unroll
+        for (int i = 0; i < S::NS; ++i) *(u32x4*)(buf + i * S::kSlab + l_off) = regs[i];
+    };
+    fetch(t_begin);     // requested ahead of the weights, so the first tile does not queue behind them
+
+    // The weights: fragment (io, kk) = rows ch0 + io*16 + x16, contraction slots kk*32 + q*8 .. +7.
+    // Read straight from memory in that shape every lane would touch its own cache line (64 address
+    // cycles per instruction), so the workgroup's rows are copied slab by slab in row order -- 8 lanes
+    // per 128-byte row segment -- through the token buffers, and picked up as fragments from there.
+    Vec wf[S::IO][KCH];
+    {
+        const BufRsrc wres = make_rsrc(w, (long)c_out * row_bytes);
+        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab: 6
+        u32x4 wr[S::NS][kWV];
+        unsigned base[kWV];
+#pragma unroll
+        for (int i = 0; i < kWV; ++i) {
+            const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
+            base[i] = row < c_out ? (unsigned)ep.row_of(row) * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
+        }
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl)
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
+                                                 ? base[i] + sl * 128 : kOobOffset, 0);
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl) {
+            if (sl) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl][i];
+            __syncthreads();
+#pragma unroll
+            for (int io = 0; io < S::IO; ++io)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wf[io][2 * sl + h] = __builtin_bit_cast(
+                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + (h * 4 + q) * 16));
+        }
+        __syncthreads();
+    }
+
+    f32x4 acc[S::IO][S::JT];
+    char* stage = lds + S::kLds - (S::kWaves - wave) * S::kStageWave;
+    const char* frag_base = lds + x16 * S::kRow + q * 16;
+
+    park(lds);
+    __syncthreads();
+    int cur = 0;
+    for (long tile = t_begin; tile < t_end; ++tile) {
+        const char* here = frag_base + cur * S::kBuf;
+        fetch(tile + 1);                       // past the end: a zero-length resource, no traffic
+#pragma unroll
+        for (int io = 0; io < S::IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // token operand fragments, requested two contraction chunks ahead of their use
+        Vec bf[3][S::JT];
+        auto read_b = [&](int kk) {
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt)
+                bf[kk % 3][jt] = __builtin_bit_cast(
+                    Vec, *(const u32x4*)(here + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
+        };
+        read_b(0);
+        read_b(1);
+#pragma unroll
+        for (int kk = 0; kk < KCH; ++kk) {
+            if (kk + 2 < KCH) read_b(kk + 2);
+#pragma unroll
+            for (int io = 0; io < S::IO; ++io)
+#pragma unroll
+                for (int jt = 0; jt < S::JT; ++jt)
+                    acc[io][jt] = Traits<T>::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
+        }
+        park(lds + (cur ^ 1) * S::kBuf);       // the other buffer was last read before the previous barrier
+
+        // results: 16 tokens x 48 channels at a time through this wave's staging rows, then 16-byte
+        // stores that cover whole runs of a token's channels
+        const auto out = ep.tile(tile * S::TB);
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int io = 0; io < S::IO; ++io)
+                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, frag_from_f32<T>(acc[io][jt]));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row: 6
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int v = lane + 64 * i;
+                if (v < 16 * kVecRow) {
+                    const int row = v / kVecRow, cv = v % kVecRow;
+                    const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
+                    out.store(ch0, ch0 + S::kChanWave, jt * 16 + row, ch0 + cv * 8, val);
+                }
+            }
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+}
+
+template <class T, int KCH, class Epilogue>
+hipError_t run_project_ws(const void* x, const void* w, long n_tokens, int c_in, int c_out, Epilogue ep,
+                          hipStream_t stream) {
+    typedef WsShape<T, KCH> S;
+    const int n_cg = (c_out + S::kChanBlock - 1) / S::kChanBlock;
+    const long n_tt = (n_tokens + S::TB - 1) / S::TB;
+    if (n_tt <= 0 || n_tt * n_cg > 0x7fffffffL) return hipErrorInvalidValue;
+    if ((long)c_out * c_in * 2 >= 0x7fffffffL) return hipErrorInvalidValue;
+    // kResident workgroups per CU; the channel groups of one token range sit next to each other
+    const long slots = (long)compute_units() * S::kResident;
+    const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
+    const long tiles_per_block = (n_tt + groups - 1) / groups;
+    const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
+    const hipError_t e = hipFuncSetAttribute((const void*)project_ws_kernel<T, KCH, Epilogue>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, S::kLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((project_ws_kernel<T, KCH, Epilogue>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
+                       stream, (const T*)x, (const T*)w, n_tokens, c_in, c_out, n_cg, n_tt, tiles_per_block, ep);
+    return hipGetLastError();
+}
+
 #ifndef MSLA_PROJ_RESIDENT
 #define MSLA_PROJ_RESIDENT 1
 #endif
@@ -232,6 +424,13 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
 template <class T, class Epilogue>
 hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, int c_out, Epilogue ep,
                        hipStream_t stream) {
+    if constexpr (sizeof(T) == 2) {
+        // short contraction: weights stay in registers
+#ifndef MSLA_PROJ_NO_WS
+        if (c_in <= 128) return run_project_ws<T, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+        if (c_in <= 256) return run_project_ws<T, 8, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+#endif
+    }
     typedef ProjTile<T> G;
     const int n_rb = (c_out + G::BR - 1) / G::BR;
     const long n_cb = (n_tokens + G::BC - 1) / G::BC;
@@ -239,7 +438,7 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
     if (n_tiles <= 0 || n_tiles > 0x7fffffffL) return hipErrorInvalidValue;
     // the weights are addressed with 32-bit byte offsets from their base, a token tile's rows too
     if ((long)c_out * c_in * (long)sizeof(T) >= 0x7fffffffL) return hipErrorInvalidValue;
-    // one resident workgroup per CU (two LDS buffers of 55 KB); whole channel-block groups per workgroup
+    // one resident workgroup per CU (two LDS buffers of 60 KB); whole channel-block groups per workgroup
     const long cus = (long)compute_units() * MSLA_PROJ_RESIDENT;
     long per = (n_tiles + cus - 1) / cus;
     per = (per + n_rb - 1) / n_rb * n_rb;
