@@ -180,6 +180,289 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
                 [out, c_out](long tok, int oc, f32x4 v) { store_frag<T>(out + tok * c_out + oc, frag_from_f32<T>(v)); });
 }
 
+// ------------------------------------------- att fused into projection, weight-stationary
+// The same fusion for a contraction of at most 512 slots (n_hb <= 2*KCH head-branches): a wave
+// keeps the projection weights of its IO*16 output channels in registers for the whole kernel, and
+// the (scaled) state operands of its own KCH/4 head-branches for as long as the image lasts.  A
+// workgroup of 8 waves owns 8*IO*16 output channels and walks over tiles of 32 tokens of one image:
+// every wave makes the attention rows of its head-branches for the tile -- Q fragments straight
+// from memory, two MFMAs per 16 tokens and head-branch -- and writes them to the tile in LDS;
+// after the barrier every wave reads the whole tile as MFMA operands against its weights.
+// fp16 double-buffers the tile, so the attention rows of tile t+1 are made while the matrix cores
+// work on tile t (one barrier per tile); bf16 needs the space for the hi and lo tiles.
+template <class T, int KCH, int IO>
+struct WsApply {
+    static_assert(sizeof(T) == 2 && KCH % 4 == 0, "16-bit elements; whole head-branch quadruples");
+    static constexpr bool kHiLo = Traits<T>::kHiLo;
+    static constexpr int kWaves = 8, kThreads = 512;
+    static constexpr int JT = 2, TB = JT * 16;           // tokens per tile
+    static constexpr int HBW = KCH / 4;                  // head-branches per wave
+    static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
+    static constexpr int NS = KCH / 2;                   // 128-byte slabs per attention row
+    static constexpr int kRow = 160;
+    static constexpr int kSlab = TB * kRow;
+    static constexpr int kBuf = NS * kSlab;              // one attention tile
+    static constexpr int kStageRow = kChanWave * 2 + 16;
+    static constexpr int kStageWave = 16 * kStageRow;
+    static constexpr int kWeightStage = kChanBlock * kRow;
+    static constexpr int kTiles = 2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage;
+    static constexpr int kLds = kTiles + kWaves * kStageWave;
+};
+
+template <class T, int KCH, int IO>
+__global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restrict__ q_ms,
+                                                               const char* __restrict__ kvfrag,
+                                                               const float* __restrict__ kvscale,
+                                                               const T* __restrict__ w_proj, T* __restrict__ out,
+                                                               int N, int n_hb, int c_out, int n_cg,
+                                                               int tiles_per_image, long n_tt,
+                                                               long tiles_per_block, float eps) {
+    typedef WsApply<T, KCH, IO> S;
+    typedef Traits<T> Tr;
+    typedef typename Tr::Vec Vec;
+    typedef typename Tr::Frag Frag;
+    constexpr bool kHiLo = S::kHiLo;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const unsigned L = xcd_remap(blockIdx.x, gridDim.x);
+    const int cg = (int)(L % (unsigned)n_cg);
+    const long t_begin = (long)(L / (unsigned)n_cg) * tiles_per_block;
+    const long t_end = t_begin + tiles_per_block < n_tt ? t_begin + tiles_per_block : n_tt;
+    if (t_begin >= t_end) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = lane_id(), x16 = lane & 15, q = lane >> 4;
+    const int K = n_hb * 16;
+    const unsigned row_bytes = (unsigned)K * 2u;
+    const int ch0 = cg * S::kChanBlock + wave * S::kChanWave;
+
+    // weights -> registers, copied in row order through LDS (see the projection kernel)
+    Vec wf[IO][KCH];
+    {
+        const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
+        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
+        unsigned base[kWV];
+#pragma unroll
+        for (int i = 0; i < kWV; ++i) {
+            const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
+            base[i] = row < c_out ? (unsigned)row * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
+        }
+        u32x4 wr[2][kWV];
+        auto wload = [&](int sl) {
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                wr[sl & 1][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
+                                                     ? base[i] + sl * 128 : kOobOffset, 0);
+        };
+        wload(0);
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl) {
+            if (sl + 1 < S::NS) wload(sl + 1);
+            if (sl) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl & 1][i];
+            __syncthreads();
+#pragma unroll
+            for (int io = 0; io < IO; ++io)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wf[io][2 * sl + h] = __builtin_bit_cast(
+                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + (h * 4 + q) * 16));
+        }
+        __syncthreads();
+    }
+
+    // this wave's head-branches: state operands and eps*scale, reloaded when the image changes
+    Vec a_kv[S::HBW], a_ks[S::HBW];
+    float eps_s[S::HBW];
+    int img = -1;
+    auto load_state = [&](int b) {
+#pragma unroll
+        for (int j = 0; j < S::HBW; ++j) {
+            const int hb = wave * S::HBW + j;
+            const long sid = (long)b * n_hb + (hb < n_hb ? hb : 0);
+            a_kv[j] = __builtin_bit_cast(Vec, *(const u32x4*)(kvfrag + sid * 2048 + lane * 16));
+            a_ks[j] = __builtin_bit_cast(Vec, *(const u32x4*)(kvfrag + sid * 2048 + 1024 + lane * 16));
+            eps_s[j] = eps * kvscale[sid];
+        }
+        img = b;
+    };
+
+    // Q fragments of a tile: unit (jt, j) = 16 tokens x head-branch wave*HBW + j; a lane holds
+    // channels 4q..4q+3 of its token (8 bytes).  Rows past the image's last token read as zero.
+    Frag qr[S::JT][S::HBW];
+    auto tile_origin = [&](long tile, int& b, int& n0) {
+        b = (int)(tile / tiles_per_image);
+        n0 = (int)(tile % tiles_per_image) * S::TB;
+    };
+    auto fetch_q = [&](long tile) {
+        int b, n0;
+        tile_origin(tile, b, n0);
+        const long tok0 = (long)b * N + n0;
+        const int rows = tile < t_end ? (N - n0 < S::TB ? N - n0 : S::TB) : 0;
+        const BufRsrc qres = make_rsrc(q_ms + tok0 * K, (long)rows * row_bytes);
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt)
+#pragma unroll
+            for (int j = 0; j < S::HBW; ++j) {
+                const int hb = wave * S::HBW + j;
+                const unsigned off = hb < n_hb ? (unsigned)(jt * 16 + x16) * row_bytes + hb * 32 + q * 8 : kOobOffset;
+                const u32x2 v = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(qres, (int)off, 0, 0));
+                qr[jt][j] = __builtin_bit_cast(Frag, v);
+            }
+    };
+    // attention rows of unit (jt, j) from qr -> tile(s) in LDS
+    auto att_one = [&](char* hi_tile, char* lo_tile, int jt, int j) {
+        const int hb = wave * S::HBW + j;
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        const Frag qf = frag_relu<T>(qr[jt][j]);
+        Vec b;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { b[r] = qf[r]; b[4 + r] = qf[r]; }   // pairs with {hi, lo} of the state
+        const f32x4 num = Tr::mma_vec(z, a_kv[j], b);
+        const f32x4 den = Tr::mma_vec(z, a_ks[j], b);
+        const float inv = 1.0f / (den[0] + eps_s[j]);
+        f32x4 o = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
+        if (hb >= n_hb) o = z;
+        const int off = (hb >> 2) * S::kSlab + (jt * 16 + x16) * S::kRow + (hb & 3) * 32 + q * 8;
+        if constexpr (kHiLo) {
+            Frag hi, lo;
+            frag_split<T>(o, hi, lo);
+            store_frag<T>(hi_tile + off, hi);
+            store_frag<T>(lo_tile + off, lo);
+        } else {
+            store_frag<T>(hi_tile + off, frag_from_f32<T>(o));
+        }
+    };
+
+    f32x4 acc[IO][S::JT];
+    char* stage = lds + S::kTiles + wave * S::kStageWave;
+    const int frag_off = x16 * S::kRow + q * 16;
+    auto mma_chunk = [&](const char* tile, int kk) {
+        Vec bf[S::JT];
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt)
+            bf[jt] = __builtin_bit_cast(
+                Vec, *(const u32x4*)(tile + frag_off + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
+#pragma unroll
+        for (int io = 0; io < IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[jt]);
+    };
+    auto epilogue = [&](long tile) {
+        int b, n0;
+        tile_origin(tile, b, n0);
+        const long tok0 = (long)b * N + n0;
+        const int rows = N - n0 < S::TB ? N - n0 : S::TB;
+        const unsigned out_row = (unsigned)c_out * 2u;
+        const BufRsrc ores = make_rsrc(out + tok0 * c_out, (long)rows * out_row);
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int io = 0; io < IO; ++io)
+                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, frag_from_f32<T>(acc[io][jt]));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row
+            if (lane < 16 * kVecRow) {
+                const int row = lane / kVecRow, cv = lane % kVecRow;
+                const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
+                const int oc = ch0 + cv * 8;
+                buf_store16(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
+            }
+        }
+    };
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int io = 0; io < IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto image_of = [&](long tile) { return (int)(tile / tiles_per_image); };
+
+    char* tile0 = lds;
+    char* tile1 = lds + S::kBuf;
+    if constexpr (!kHiLo) {
+        // prologue: attention rows of the first tile
+        fetch_q(t_begin);
+        load_state(image_of(t_begin));
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt)
+#pragma unroll
+            for (int j = 0; j < S::HBW; ++j) att_one(tile0, nullptr, jt, j);
+        fetch_q(t_begin + 1);
+        __syncthreads();
+        int cur = 0;
+        for (long tile = t_begin; tile < t_end; ++tile) {
+            const char* here = cur ? tile1 : tile0;
+            char* next = cur ? tile0 : tile1;
+            const bool more = tile + 1 < t_end;
+            if (more && image_of(tile + 1) != img) load_state(image_of(tile + 1));
+            zero_acc();
+            // the attention rows of the next tile are dealt out between the chunks of this tile's
+            // matrix instructions, so their vector arithmetic runs in the MFMAs' shadow
+            constexpr int kUnits = S::JT * S::HBW;
+#pragma unroll
+            for (int kk = 0; kk < KCH; ++kk) {
+                mma_chunk(here, kk);
+                if (kk % (KCH / kUnits) == 0 && more) {
+                    const int u = kk / (KCH / kUnits);
+                    att_one(next, nullptr, u / S::HBW, u % S::HBW);
+                }
+            }
+            if (more) fetch_q(tile + 2);
+            epilogue(tile);
+            __syncthreads();
+            cur ^= 1;
+        }
+    } else {
+        fetch_q(t_begin);
+        for (long tile = t_begin; tile < t_end; ++tile) {
+            if (image_of(tile) != img) load_state(image_of(tile));
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt)
+#pragma unroll
+                for (int j = 0; j < S::HBW; ++j) att_one(tile0, tile1, jt, j);
+            fetch_q(tile + 1);
+            __syncthreads();
+            zero_acc();
+#pragma unroll
+            for (int kk = 0; kk < KCH; ++kk) {
+                mma_chunk(tile0, kk);
+                mma_chunk(tile1, kk);
+            }
+            epilogue(tile);
+            __syncthreads();
+        }
+    }
+}
+
+template <class T, int KCH, int IO>
+hipError_t run_apply_project_ws(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
+                                void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
+                                hipStream_t stream) {
+    typedef WsApply<T, KCH, IO> S;
+    const int n_cg = (c_out + S::kChanBlock - 1) / S::kChanBlock;
+    const int tiles_per_image = (N + S::TB - 1) / S::TB;
+    const long n_tt = (n_tokens / N) * tiles_per_image;
+    if (n_tt <= 0 || n_tt * n_cg > 0x7fffffffL) return hipErrorInvalidValue;
+    if ((long)c_out * n_hb * 32 >= 0x7fffffffL) return hipErrorInvalidValue;
+    const long slots = compute_units();
+    const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
+    const long tiles_per_block = (n_tt + groups - 1) / groups;
+    const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
+    const hipError_t e = hipFuncSetAttribute((const void*)apply_project_ws_kernel<T, KCH, IO>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, S::kLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((apply_project_ws_kernel<T, KCH, IO>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
+                       stream, (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb,
+                       c_out, n_cg, tiles_per_image, n_tt, tiles_per_block, eps);
+    return hipGetLastError();
+}
+
 template <class T>
 hipError_t run_apply(const void* q_ms, const void* kvfrag, const float* kvscale, void* att, long n_tokens,
                      int N, int n_hb, float eps, hipStream_t stream) {
@@ -196,6 +479,22 @@ template <class T>
 hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
                              void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
                              hipStream_t stream) {
+#ifndef MSLA_APPLY_NO_WS
+    if constexpr (sizeof(T) == 2) {
+        // short contraction: weights and states stay in registers
+        if (n_hb <= 32) {
+            const bool narrow = c_out <= 128;
+            if (n_hb <= 16)
+                return narrow ? run_apply_project_ws<T, 8, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
+                              : run_apply_project_ws<T, 8, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+            if (n_hb <= 24)
+                return narrow ? run_apply_project_ws<T, 12, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
+                              : run_apply_project_ws<T, 12, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+            return narrow ? run_apply_project_ws<T, 16, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
+                          : run_apply_project_ws<T, 16, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+        }
+    }
+#endif
     typedef ApplyTile<T> G;
     const int bpi = (N + G::BC - 1) / G::BC;
     const int n_rb = (c_out + G::BR - 1) / G::BR;
