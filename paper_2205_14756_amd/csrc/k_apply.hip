@@ -206,7 +206,9 @@ struct WsApply {
     static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kWeightStage = kChanBlock * kRow;
     static constexpr int kTiles = 2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage;
-    static constexpr int kLds = kTiles + kWaves * kStageWave;
+    static constexpr int kQV = NS / 2;                   // 16-byte vectors per thread of a Q tile
+    static constexpr int kLds = kTiles + kBuf + kWaves * kStageWave;    // two tiles, the Q tile, staging
+    static_assert(NS % 2 == 0 && TB * 16 == kThreads, "the Q tile copy takes two slabs per pass");
 };
 
 template <class T, int KCH, int IO>
@@ -288,13 +290,16 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         img = b;
     };
 
-    // Q fragments of a tile: unit (jt, j) = 16 tokens x head-branch wave*HBW + j; a lane holds
-    // channels 4q..4q+3 of its token (8 bytes).  Rows past the image's last token read as zero.
-    Frag qr[S::JT][S::HBW];
+    // The Q tile (32 tokens x all head-branches) is copied in row order -- 8 lanes per 128-byte row
+    // segment; read as fragments straight from memory every lane would touch its own row -- into
+    // LDS, laid out like the attention tile.  Rows past the image's last token read as zero.
+    char* qbuf = lds + S::kTiles;
+    u32x4 qv[S::kQV];
     auto tile_origin = [&](long tile, int& b, int& n0) {
         b = (int)(tile / tiles_per_image);
         n0 = (int)(tile % tiles_per_image) * S::TB;
     };
+    const int q_slab = threadIdx.x >> 8, q_row = (threadIdx.x >> 3) & 31, q_chunk = threadIdx.x & 7;
     auto fetch_q = [&](long tile) {
         int b, n0;
         tile_origin(tile, b, n0);
@@ -302,29 +307,43 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         const int rows = tile < t_end ? (N - n0 < S::TB ? N - n0 : S::TB) : 0;
         const BufRsrc qres = make_rsrc(q_ms + tok0 * K, (long)rows * row_bytes);
 #pragma unroll
-        for (int jt = 0; jt < S::JT; ++jt)
-#pragma unroll
-            for (int j = 0; j < S::HBW; ++j) {
-                const int hb = wave * S::HBW + j;
-                const unsigned off = hb < n_hb ? (unsigned)(jt * 16 + x16) * row_bytes + hb * 32 + q * 8 : kOobOffset;
-                const u32x2 v = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(qres, (int)off, 0, 0));
-                qr[jt][j] = __builtin_bit_cast(Frag, v);
-            }
+        for (int i = 0; i < S::kQV; ++i) {
+            const unsigned col = (2 * i + q_slab) * 128 + q_chunk * 16;
+            qv[i] = buf_load16(qres, col < row_bytes ? q_row * row_bytes + col : kOobOffset, 0);
+        }
     };
-    // attention rows of unit (jt, j) from qr -> tile(s) in LDS
-    auto att_one = [&](char* hi_tile, char* lo_tile, int jt, int j) {
-        const int hb = wave * S::HBW + j;
+    auto park_q = [&]() {
+#pragma unroll
+        for (int i = 0; i < S::kQV; ++i)
+            *(u32x4*)(qbuf + (2 * i + q_slab) * S::kSlab + q_row * S::kRow + q_chunk * 16) = qv[i];
+    };
+    // Attention rows of unit u = (jt, j) = 16 tokens x head-branch wave*HBW + j, Q tile -> tile(s) in
+    // LDS, a lane handling channels 4q..4q+3 of its token.  The unit is cut into three stages
+    // (request Q; rectify and issue the two MFMAs; normalise and store) that the callers place in
+    // different slots of their instruction stream, so no stage waits for the one before it.
+    constexpr int kUnits = S::JT * S::HBW;
+    Frag att_q[2];
+    f32x4 att_num[2], att_den[2];
+    auto unit_off = [&](int u) {
+        const int hb = wave * S::HBW + u % S::HBW;
+        return (hb >> 2) * S::kSlab + ((u / S::HBW) * 16 + x16) * S::kRow + (hb & 3) * 32 + q * 8;
+    };
+    auto att_a = [&](int u) { att_q[u & 1] = load_frag<T>((const T*)(qbuf + unit_off(u))); };
+    auto att_b = [&](int u) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        const Frag qf = frag_relu<T>(qr[jt][j]);
+        const Frag qf = frag_relu<T>(att_q[u & 1]);
         Vec b;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { b[r] = qf[r]; b[4 + r] = qf[r]; }   // pairs with {hi, lo} of the state
-        const f32x4 num = Tr::mma_vec(z, a_kv[j], b);
-        const f32x4 den = Tr::mma_vec(z, a_ks[j], b);
-        const float inv = 1.0f / (den[0] + eps_s[j]);
-        f32x4 o = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
-        if (hb >= n_hb) o = z;
-        const int off = (hb >> 2) * S::kSlab + (jt * 16 + x16) * S::kRow + (hb & 3) * 32 + q * 8;
+        att_num[u & 1] = Tr::mma_vec(z, a_kv[u % S::HBW], b);
+        att_den[u & 1] = Tr::mma_vec(z, a_ks[u % S::HBW], b);
+    };
+    auto att_c = [&](int u, char* hi_tile, char* lo_tile) {
+        const int hb = wave * S::HBW + u % S::HBW;
+        const f32x4 num = att_num[u & 1];
+        const float inv = hb < n_hb ? __builtin_amdgcn_rcpf(att_den[u & 1][0] + eps_s[u % S::HBW]) : 0.f;
+        const f32x4 o = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
+        const int off = unit_off(u);
         if constexpr (kHiLo) {
             Frag hi, lo;
             frag_split<T>(o, hi, lo);
@@ -334,20 +353,34 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             store_frag<T>(hi_tile + off, frag_from_f32<T>(o));
         }
     };
+    // all units of a tile, the stages of neighbouring units overlapped
+    auto att_all = [&](char* hi_tile, char* lo_tile) {
+        att_a(0);
+#pragma unroll
+        for (int u = 0; u < kUnits; ++u) {
+            if (u + 1 < kUnits) att_a(u + 1);
+            att_b(u);
+            if (u > 0) att_c(u - 1, hi_tile, lo_tile);
+        }
+        att_c(kUnits - 1, hi_tile, lo_tile);
+    };
 
     f32x4 acc[IO][S::JT];
-    char* stage = lds + S::kTiles + wave * S::kStageWave;
+    char* stage = lds + S::kTiles + S::kBuf + wave * S::kStageWave;
     const int frag_off = x16 * S::kRow + q * 16;
-    auto mma_chunk = [&](const char* tile, int kk) {
-        Vec bf[S::JT];
+    // token-operand fragments are requested two contraction chunks ahead of their use
+    Vec bf[3][S::JT];
+    auto read_b = [&](const char* tile, int kk) {
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt)
-            bf[jt] = __builtin_bit_cast(
+            bf[kk % 3][jt] = __builtin_bit_cast(
                 Vec, *(const u32x4*)(tile + frag_off + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
+    };
+    auto mma_chunk = [&](int kk) {
 #pragma unroll
         for (int io = 0; io < IO; ++io)
 #pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[jt]);
+            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
     };
     auto epilogue = [&](long tile) {
         int b, n0;
@@ -389,31 +422,42 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         // prologue: attention rows of the first tile
         fetch_q(t_begin);
         load_state(image_of(t_begin));
-#pragma unroll
-        for (int jt = 0; jt < S::JT; ++jt)
-#pragma unroll
-            for (int j = 0; j < S::HBW; ++j) att_one(tile0, nullptr, jt, j);
+        park_q();
         fetch_q(t_begin + 1);
+        __syncthreads();
+        att_all(tile0, nullptr);
         __syncthreads();
         int cur = 0;
         for (long tile = t_begin; tile < t_end; ++tile) {
             const char* here = cur ? tile1 : tile0;
             char* next = cur ? tile0 : tile1;
-            const bool more = tile + 1 < t_end;
-            if (more && image_of(tile + 1) != img) load_state(image_of(tile + 1));
+            if (tile + 1 < t_end && image_of(tile + 1) != img) load_state(image_of(tile + 1));
+            park_q();                  // Q of tile + 1 (zeros past the last tile)
+            fetch_q(tile + 2);
+            __syncthreads();
             zero_acc();
-            // the attention rows of the next tile are dealt out between the chunks of this tile's
-            // matrix instructions, so their vector arithmetic runs in the MFMAs' shadow
-            constexpr int kUnits = S::JT * S::HBW;
+            // The attention rows of the next tile are dealt out between the chunks of this tile's
+            // matrix instructions -- one unit per KCH/kUnits chunks, its three stages in consecutive
+            // slots -- so their latencies and vector arithmetic run in the MFMAs' shadow.  Past the
+            // last tile this makes rows of zeros that nobody reads.
+            constexpr int kPer = KCH / kUnits;
+            static_assert(kPer == 2, "one unit per two chunks");
+            read_b(here, 0);
+            read_b(here, 1);
+            att_a(0);
 #pragma unroll
             for (int kk = 0; kk < KCH; ++kk) {
-                mma_chunk(here, kk);
-                if (kk % (KCH / kUnits) == 0 && more) {
-                    const int u = kk / (KCH / kUnits);
-                    att_one(next, nullptr, u / S::HBW, u % S::HBW);
+                if (kk + 2 < KCH) read_b(here, kk + 2);
+                const int u = kk / 2;
+                if (kk % 2 == 0) {
+                    att_b(u);
+                    if (u + 1 < kUnits) att_a(u + 1);
+                } else {
+                    att_c(u, next, nullptr);
                 }
+                mma_chunk(kk);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (more) fetch_q(tile + 2);
             epilogue(tile);
             __syncthreads();
             cur ^= 1;
@@ -422,20 +466,29 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         fetch_q(t_begin);
         for (long tile = t_begin; tile < t_end; ++tile) {
             if (image_of(tile) != img) load_state(image_of(tile));
-#pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt)
-#pragma unroll
-                for (int j = 0; j < S::HBW; ++j) att_one(tile0, tile1, jt, j);
+            park_q();
             fetch_q(tile + 1);
+            __syncthreads();           // Q tile complete; every wave is done with the previous tiles
+            att_all(tile0, tile1);
             __syncthreads();
             zero_acc();
+            read_b(tile0, 0);
 #pragma unroll
             for (int kk = 0; kk < KCH; ++kk) {
-                mma_chunk(tile0, kk);
-                mma_chunk(tile1, kk);
+                // hi and lo tiles alternate through the fragment ring: slot 2*kk is hi, 2*kk+1 lo
+                Vec lo[S::JT];
+#pragma unroll
+                for (int jt = 0; jt < S::JT; ++jt)
+                    lo[jt] = __builtin_bit_cast(
+                        Vec, *(const u32x4*)(tile1 + frag_off + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
+                if (kk + 1 < KCH) read_b(tile0, kk + 1);
+                mma_chunk(kk);
+#pragma unroll
+                for (int io = 0; io < IO; ++io)
+#pragma unroll
+                    for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], lo[jt]);
             }
             epilogue(tile);
-            __syncthreads();
         }
     }
 }
