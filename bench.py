@@ -173,15 +173,33 @@ def main():
     parity = None
     if not args.no_cpu_baseline:
         from oracle import msla_oracle as orc
-        t1 = time.perf_counter()
-        ref = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads, wl.head_dim,
-                          wl.scales, wl.eps)
-        cpu_s = time.perf_counter() - t1
-        cpu = {"value": round(wl.tokens / cpu_s, 1), "unit": "tokens/s", "cores": orc.num_threads(),
-               "kind": "oracle", "sample": f"the full {wl.name} batch ({wl.tokens} tokens), one pass, "
-                                            f"{cpu_s:.2f} s wall"}
+        # whole passes over the full batch until about ten seconds of CPU work have been timed
+        passes, cpu_s = 0, 0.0
+        while cpu_s < 10.0:
+            t1 = time.perf_counter()
+            ref = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads, wl.head_dim,
+                              wl.scales, wl.eps)
+            cpu_s += time.perf_counter() - t1
+            passes += 1
+        cpu = {"value": round(wl.tokens * passes / cpu_s, 1), "unit": "tokens/s", "cores": orc.num_threads(),
+               "kind": "oracle", "sample": f"{passes} passes over the full {wl.name} batch ({wl.tokens} tokens "
+                                            f"each), {cpu_s:.2f} s wall in total"}
+        # Parity of the benchmarked output against the plain fp64 oracle (untimed).  Eq. (3) is
+        # discontinuous where a token's rectified Q row is all zero (0/0 vs. a unit-size quotient),
+        # so a token whose only positive Q component is within a few roundoffs of zero may flip
+        # under 16-bit storage; the figure is reported over all tokens and over the tokens whose
+        # gate margin is at least 64 unit roundoffs.
         got = out.to(torch.float64).cpu().numpy()
-        parity = float(np.abs(got - ref).max() / np.abs(ref).max())
+        err = np.abs(got - ref).reshape(wl.B * wl.H * wl.W, -1).max(-1)
+        scale = np.abs(ref).max()
+        _, parts = orc.forward_staged(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads,
+                                      wl.head_dim, wl.scales, wl.eps, return_parts=True)
+        margin = orc.gate_margin(parts["q_tokens"], parts["kv"], wl.heads, wl.head_dim).min(-1).reshape(-1)
+        unit_roundoff = {"f32": 2.0 ** -24, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[wl.dtype]
+        well = margin >= 64 * unit_roundoff
+        parity = {"all_tokens": float(err.max() / scale),
+                  "gate_conditioned": float(err[well].max() / scale) if well.any() else 0.0,
+                  "gate_conditioned_fraction": float(well.mean())}
 
     line = {
         "metric": "MSLA module tokens/s (64x128 tokens, C=256, fp16)", "value": round(tokens_per_s, 1),

@@ -237,42 +237,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     const unsigned row_bytes = (unsigned)K * 2u;
     const int ch0 = cg * S::kChanBlock + wave * S::kChanWave;
 
-    // weights -> registers, copied in row order through LDS (see the projection kernel)
     Vec wf[IO][KCH];
-    {
-        const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
-        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
-        unsigned base[kWV];
-#pragma unroll
-        for (int i = 0; i < kWV; ++i) {
-            const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
-            base[i] = row < c_out ? (unsigned)row * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
-        }
-        u32x4 wr[2][kWV];
-        auto wload = [&](int sl) {
-#pragma unroll
-            for (int i = 0; i < kWV; ++i)
-                wr[sl & 1][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
-                                                     ? base[i] + sl * 128 : kOobOffset, 0);
-        };
-        wload(0);
-#pragma unroll
-        for (int sl = 0; sl < S::NS; ++sl) {
-            if (sl + 1 < S::NS) wload(sl + 1);
-            if (sl) __syncthreads();
-#pragma unroll
-            for (int i = 0; i < kWV; ++i)
-                *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl & 1][i];
-            __syncthreads();
-#pragma unroll
-            for (int io = 0; io < IO; ++io)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wf[io][2 * sl + h] = __builtin_bit_cast(
-                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + (h * 4 + q) * 16));
-        }
-        __syncthreads();
-    }
 
     // this wave's head-branches: state operands and eps*scale, reloaded when the image changes
     Vec a_kv[S::HBW], a_ks[S::HBW];
@@ -416,11 +381,47 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     };
     auto image_of = [&](long tile) { return (int)(tile / tiles_per_image); };
 
+    fetch_q(t_begin);      // requested ahead of the weights, so the first tile does not queue behind them
+    // weights -> registers, copied in row order through LDS (see the projection kernel)
+    {
+        const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
+        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
+        unsigned base[kWV];
+#pragma unroll
+        for (int i = 0; i < kWV; ++i) {
+            const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
+            base[i] = row < c_out ? (unsigned)row * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
+        }
+        // all slabs are requested at once (the registers they wait in are the ones the fragments
+        // move into), so the memory latency is paid once
+        u32x4 wr[S::NS][kWV];
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl)
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
+                                                 ? base[i] + sl * 128 : kOobOffset, 0);
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl) {
+            if (sl) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl][i];
+            __syncthreads();
+#pragma unroll
+            for (int io = 0; io < IO; ++io)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wf[io][2 * sl + h] = __builtin_bit_cast(
+                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + (h * 4 + q) * 16));
+        }
+        __syncthreads();
+    }
+
     char* tile0 = lds;
     char* tile1 = lds + S::kBuf;
     if constexpr (!kHiLo) {
         // prologue: attention rows of the first tile
-        fetch_q(t_begin);
         load_state(image_of(t_begin));
         park_q();
         fetch_q(t_begin + 1);
@@ -463,7 +464,6 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             cur ^= 1;
         }
     } else {
-        fetch_q(t_begin);
         for (long tile = t_begin; tile < t_end; ++tile) {
             if (image_of(tile) != img) load_state(image_of(tile));
             park_q();
@@ -475,7 +475,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             read_b(tile0, 0);
 #pragma unroll
             for (int kk = 0; kk < KCH; ++kk) {
-                // hi and lo tiles alternate through the fragment ring: slot 2*kk is hi, 2*kk+1 lo
+                // the hi fragments come through the ring, one chunk ahead; the lo ones are read here
                 Vec lo[S::JT];
 #pragma unroll
                 for (int jt = 0; jt < S::JT; ++jt)
