@@ -59,7 +59,7 @@ struct MLds {
     static constexpr int kPlanarBytes = 48 * kChanBytes;
     static constexpr int kTokStride = 80;                      // transposition buffer: 16 tokens x 16 fp32 (+pad)
     static constexpr int kTransBytes = 16 * kTokStride;
-    static constexpr int kBytes = 2 * kPlanarBytes + kSweepWaves * kTransBytes;   // two tiles in flight
+    static constexpr int kBytes = 2 * kPlanarBytes + kSweepWaves * 2 * kTransBytes;   // two tiles in flight; two transposition buffers per sweeping wave
     static_assert(LW <= 36 && (kChanBytes / 4) % 32 == 8, "LDS layout");
 };
 
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const int sw = (wave - 4) & (kSweepWaves - 1);   // sweeping wave index
     const int x16 = lane & 15, q = lane >> 4;      // 16x16 MFMA view of the lane
     const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block (channel), row/column inside it
-    char* trans = lds + 2 * L::kPlanarBytes + sw * L::kTransBytes;
+    char* trans = lds + 2 * L::kPlanarBytes + sw * 2 * L::kTransBytes;
 
     const T* wdw = (const T*)a.w_dw + (long)h * 48 * KS * KS;
     const T* wgp = (const T*)a.w_gpw + (long)h * 48 * 16;
@@ -301,15 +301,94 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         const int gy0 = ty0 + R * part;
         const int gx0 = tx0 + col0;
         Frag aggK[R], aggK_lo[R];
+        // The three passes (K, V, Q) form one flat, fully unrolled sequence of input rows.  A finished
+        // output row goes through three stages in three consecutive iterations, so that no stage
+        // waits for the one before it: (1) hand the row to LDS for transposition (K, Q) or to the
+        // lane permutation (V); (2) pick it up in operand layout and issue the grouped-1x1 / state
+        // MFMA; (3) rectify, pack, store.  Two transposition buffers alternate.
+        constexpr int NR = R + 2 * P;
+        f32x4 acc[KS];
+        f32x4 s1v[2], s2v[2];             // V after the permutation; MFMA results awaiting stage 3
+        auto pass_t = [](int pass) { return pass == 0 ? 1 : pass == 1 ? 2 : 0; };     // K, V, Q
+        auto stage1 = [&](int it, f32x4 o) {
+            const int t = pass_t(it / NR), y = it % NR - (KS - 1);
+            const int gy = gy0 + y;
+            if (t == 1) {
+                // tokens outside the image contribute nothing: their aggregated K is made 0, which
+                // also removes their V from the state; Q rows of such tokens are simply not stored
 #pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int t = (pass == 0) ? 1 : (pass == 1) ? 2 : 0;     // K, V, Q
-            const char* src = planar + (t * 16 + blk) * L::kChanBytes + (R * part) * L::kRowBytes + col0 * 2;
-            f32x4 acc[KS];
+                for (int i = 0; i < 4; ++i)
+                    if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;
+            }
+            if (t == 2) {
+                // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
 #pragma unroll
-            for (int i = 0; i < KS; ++i) acc[i] = z;
+                for (int i = 0; i < 4; ++i) s1v[it & 1][i] = __shfl(o[i], 4 * x16 + q);
+            } else {
+                // K, Q: 16 tokens x 16 channels -> lane (token 4*xblock + i, q) with channels 4q..4q+3
+                char* tb = trans + (it & 1) * L::kTransBytes;
+                wave_lds_fence();
 #pragma unroll
-            for (int r = 0; r < R + 2 * P; ++r) {
+                for (int i = 0; i < 4; ++i) *(float*)(tb + (4 * sub + i) * L::kTokStride + blk * 4) = o[i];
+                wave_lds_fence();
+            }
+        };
+        auto stage2 = [&](int it) {
+            const int t = pass_t(it / NR), y = it % NR - (KS - 1);
+            if (t == 2) {
+                const f32x4 vf = s1v[it & 1];
+                if constexpr (Tr::kHiLo) {
+                    Frag vh, vl;
+                    frag_split<T>(vf, vh, vl);
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], vh);
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], vl);
+                    kv_agg = Tr::mma16(kv_agg, aggK_lo[y], vh);
+                } else {
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], frag_from_f32<T>(vf));
+                }
+                return;
+            }
+            const char* tb = trans + (it & 1) * L::kTransBytes;
+            const f32x4 tq = *(const f32x4*)(tb + x16 * L::kTokStride + q * 16);
+            Frag dwf, dwf_lo;
+            if constexpr (Tr::kHiLo) frag_split<T>(tq, dwf, dwf_lo);
+            else dwf = frag_from_f32<T>(tq);
+            if (t == 1) {
+                f32x4 kf = Tr::mma16(z, dwf, gpw_k);
+                if constexpr (Tr::kHiLo) kf = Tr::mma16(kf, dwf_lo, gpw_k);
+                s2v[it & 1] = kf;
+            } else {
+                f32x4 qq = Tr::mma16(z, gpw_q, dwf);
+                if constexpr (Tr::kHiLo) qq = Tr::mma16(qq, gpw_q, dwf_lo);
+                s2v[it & 1] = qq;
+            }
+        };
+        auto stage3 = [&](int it) {
+            const int t = pass_t(it / NR), y = it % NR - (KS - 1);
+            if (t == 1) {
+                const f32x4 kf = relu_bits_f32(s2v[it & 1]);       // Eq. (2): relu(K), one integer max per value
+                ks_agg += (kf[0] + kf[1]) + (kf[2] + kf[3]);
+                if constexpr (Tr::kHiLo) frag_split<T>(kf, aggK[y], aggK_lo[y]);
+                else aggK[y] = frag_from_f32<T>(kf);
+            } else if (t == 0) {
+                // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3
+                const int gy = gy0 + y;
+                const int gx = tx0 + 16 * strip + x16;
+                if (gy < a.H && gx < a.W)
+                    store_frag<T>(q_ms + (img_tok0 + (long)gy * a.W + gx) * q_ms_ts + (long)a.branch * Ct + h * 16 + q * 4,
+                                  frag_from_f32<T>(s2v[it & 1]));
+            }
+        };
+        static_for<0, 3 * NR + 2>([&](auto it_c) {
+            constexpr int it = decltype(it_c)::value;
+            if constexpr (it < 3 * NR) {
+                const int pass = it / NR, r = it % NR;
+                const int t = pass_t(pass);
+                const char* src = planar + (t * 16 + blk) * L::kChanBytes + (R * part) * L::kRowBytes + col0 * 2;
+                if (r == 0) {
+#pragma unroll
+                    for (int i = 0; i < KS; ++i) acc[i] = z;
+                }
                 const Frag d0 = load_frag<T>(src + r * L::kRowBytes);
                 const Frag d1 = load_frag<T>(src + r * L::kRowBytes + 8);
 #pragma unroll
@@ -319,64 +398,20 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                     acc[y % KS] = M4<T>::mma(toep[t][u][0], d0, acc[y % KS]);
                     acc[y % KS] = M4<T>::mma(toep[t][u][1], d1, acc[y % KS]);
                 }
-                const int y = r - (KS - 1);
-                if (y < 0) continue;
-                // ---- output row y of 16 channels x 16 tokens is complete: lane (channel blk, x-block sub)
-                // holds the 4 tokens gx0..gx0+3 of image row gy0 + y
-                f32x4 o = acc[y % KS];
-                acc[y % KS] = z;
-                const int gy = gy0 + y;
-                if (t == 1) {
-                    // tokens outside the image contribute nothing: their aggregated K is made 0, which
-                    // also removes their V from the state; Q rows of such tokens are simply not stored
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;
-                }
-                if (t == 2) {
-                    // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
-                    f32x4 vf;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) vf[i] = __shfl(o[i], 4 * x16 + q);
-                    if constexpr (Tr::kHiLo) {
-                        Frag vh, vl;
-                        frag_split<T>(vf, vh, vl);
-                        kv_agg = Tr::mma16(kv_agg, aggK[y], vh);
-                        kv_agg = Tr::mma16(kv_agg, aggK[y], vl);
-                        kv_agg = Tr::mma16(kv_agg, aggK_lo[y], vh);
-                    } else {
-                        kv_agg = Tr::mma16(kv_agg, aggK[y], frag_from_f32<T>(vf));
-                    }
-                } else {
-                    // K, Q: 16 tokens x 16 channels -> lane (token 4*xblock + i, q) with channels 4q..4q+3
-                    wave_lds_fence();
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) *(float*)(trans + (4 * sub + i) * L::kTokStride + blk * 4) = o[i];
-                    wave_lds_fence();
-                    const f32x4 tq = *(const f32x4*)(trans + x16 * L::kTokStride + q * 16);
-                    Frag dwf, dwf_lo;
-                    if constexpr (Tr::kHiLo) frag_split<T>(tq, dwf, dwf_lo);
-                    else dwf = frag_from_f32<T>(tq);
-                    if (t == 1) {
-                        f32x4 kf = Tr::mma16(z, dwf, gpw_k);
-                        if constexpr (Tr::kHiLo) kf = Tr::mma16(kf, dwf_lo, gpw_k);
-                        kf = relu_bits_f32(kf);       // Eq. (2): relu(K), one integer max per value
-                        ks_agg += (kf[0] + kf[1]) + (kf[2] + kf[3]);
-                        if constexpr (Tr::kHiLo) frag_split<T>(kf, aggK[y], aggK_lo[y]);
-                        else aggK[y] = frag_from_f32<T>(kf);
-                    } else {
-                        f32x4 qq = Tr::mma16(z, gpw_q, dwf);
-                        if constexpr (Tr::kHiLo) qq = Tr::mma16(qq, gpw_q, dwf_lo);
-                        // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3
-                        const int gx = tx0 + 16 * strip + x16;
-                        if (gy < a.H && gx < a.W)
-                            store_frag<T>(q_ms + (img_tok0 + (long)gy * a.W + gx) * q_ms_ts + (long)a.branch * Ct +
-                                              h * 16 + q * 4,
-                                          frag_from_f32<T>(qq));
-                    }
-                }
             }
-        }
+            // iteration i finishes an output row iff it is the KS-th or a later input row of its pass
+            constexpr auto has_row = [](int i) { return i >= 0 && i < 3 * NR && i % NR >= KS - 1; };
+            if constexpr (has_row(it - 1)) stage2(it - 1);
+            if constexpr (has_row(it - 2)) stage3(it - 2);
+            if constexpr (has_row(it)) {
+                // output row y of 16 channels x 16 tokens is complete: lane (channel blk, x-block sub)
+                // holds the 4 tokens gx0..gx0+3 of image row gy0 + y
+                const int y = it % NR - (KS - 1);
+                const f32x4 o = acc[y % KS];
+                acc[y % KS] = z;
+                stage1(it, o);
+            }
+        });
         }
         __syncthreads();
     }

@@ -11,6 +11,7 @@
 // ("Frag"), whatever instruction the storage type maps to.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace msla {
@@ -27,6 +28,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHeadDim = 16;            // d of Section 3.1; the only head size built
 constexpr int kStateSize = 16 * 17;     // d x (d+1) floats of the Eq. (3) state
+
+// Compile-time loop: f(std::integral_constant<int, i>) for i in [B, E).  Unlike "#pragma unroll" it
+// cannot be declined by the optimiser, so register arrays indexed by i never turn into scratch.
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
