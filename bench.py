@@ -107,8 +107,8 @@ def main():
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_cfg5.txt"))
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the module is a single-device kernel path; "
-                 "see DESIGN.md for how it would shard). Run with --gpus 1.")
+        sys.exit("bench.py: this build runs on one GPU only (the module is a single-device kernel path that "
+                 "would shard over the batch, one process per GPU, with no collective). Run with --gpus 1.")
 
     import numpy as np
     import torch
