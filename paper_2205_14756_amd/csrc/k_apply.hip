@@ -347,7 +347,19 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
             for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
     };
-    auto epilogue = [&](long tile) {
+    // Results leave in two steps.  finish() rounds a tile's accumulators into registers; flush()
+    // -- called at the top of the NEXT tile's period, after the wait for that period's Q loads and
+    // before the following loads are requested -- parks them in this wave's staging rows and writes
+    // 16-byte words.  The memory counter is in order, so a wait for loads also waits for every older
+    // store: placed there, the stores have a whole period to complete before anything waits on them.
+    Frag pend[IO][S::JT];
+    auto finish = [&]() {
+#pragma unroll
+        for (int io = 0; io < IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
+    };
+    auto flush = [&](long tile) {
         int b, n0;
         tile_origin(tile, b, n0);
         const long tok0 = (long)b * N + n0;
@@ -360,7 +372,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int io = 0; io < IO; ++io)
-                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, frag_from_f32<T>(acc[io][jt]));
+                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -434,6 +446,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             char* next = cur ? tile0 : tile1;
             if (tile + 1 < t_end && image_of(tile + 1) != img) load_state(image_of(tile + 1));
             park_q();                  // Q of tile + 1 (zeros past the last tile)
+            if (tile > t_begin) flush(tile - 1);
             fetch_q(tile + 2);
             __syncthreads();
             zero_acc();
@@ -459,14 +472,16 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
                 mma_chunk(kk);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            epilogue(tile);
+            finish();
             __syncthreads();
             cur ^= 1;
         }
+        flush(t_end - 1);
     } else {
         for (long tile = t_begin; tile < t_end; ++tile) {
             if (image_of(tile) != img) load_state(image_of(tile));
             park_q();
+            if (tile > t_begin) flush(tile - 1);
             fetch_q(tile + 1);
             __syncthreads();           // Q tile complete; every wave is done with the previous tiles
             att_all(tile0, tile1);
@@ -488,8 +503,9 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
                     for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], lo[jt]);
             }
-            epilogue(tile);
+            finish();
         }
+        flush(t_end - 1);
     }
 }
 
