@@ -185,11 +185,21 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
 // keeps the projection weights of its IO*16 output channels in registers for the whole kernel, and
 // the (scaled) state operands of its own KCH/4 head-branches for as long as the image lasts.  A
 // workgroup of 8 waves owns 8*IO*16 output channels and walks over tiles of 32 tokens of one image:
-// every wave makes the attention rows of its head-branches for the tile -- Q fragments straight
-// from memory, two MFMAs per 16 tokens and head-branch -- and writes them to the tile in LDS;
-// after the barrier every wave reads the whole tile as MFMA operands against its weights.
-// fp16 double-buffers the tile, so the attention rows of tile t+1 are made while the matrix cores
-// work on tile t (one barrier per tile); bf16 needs the space for the hi and lo tiles.
+// every wave makes the attention rows of its head-branches for the tile -- two MFMAs per 16 tokens
+// and head-branch -- and writes them to the tile in LDS; after the barrier every wave reads the
+// whole tile as MFMA operands against its weights.
+//
+// fp16 runs this as one software pipeline with a single barrier per tile: while the matrix cores
+// work through tile t (16 chunks of IO*2 MFMAs), the same instruction stream carries, dealt out
+// between the chunks, the attention rows of tile t+1 (three stages per unit), the copy of the Q
+// tile t+2 from registers to LDS, the request for Q tile t+3, and the stores of tile t-1's results.
+// Measured with the shader clock, a period that keeps those jobs in blocks of their own around the
+// MFMAs spends 60 % of its cycles outside the matrix instructions, all waves idling together.
+// bf16 needs the LDS for the hi and lo tiles and keeps the phases apart (two barriers per tile).
+//
+// LDS tiles are [128-byte slab][token][128 bytes] without padding; the 16-byte chunk index of a row
+// is XOR-ed with (row / 2) % 8, which keeps the 16-byte operand reads (16 consecutive rows of one
+// chunk), the row-order copies (8 lanes per row) and the 8-byte attention accesses conflict-free.
 template <class T, int KCH, int IO>
 struct WsApply {
     static_assert(sizeof(T) == 2 && KCH % 4 == 0, "16-bit elements; whole head-branch quadruples");
@@ -197,19 +207,24 @@ struct WsApply {
     static constexpr int kWaves = 8, kThreads = 512;
     static constexpr int JT = 2, TB = JT * 16;           // tokens per tile
     static constexpr int HBW = KCH / 4;                  // head-branches per wave
+    static constexpr int kUnits = JT * HBW;              // attention units per wave and tile
     static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
     static constexpr int NS = KCH / 2;                   // 128-byte slabs per attention row
-    static constexpr int kRow = 160;
+    static constexpr int kRow = 128;
     static constexpr int kSlab = TB * kRow;
-    static constexpr int kBuf = NS * kSlab;              // one attention tile
+    static constexpr int kBuf = NS * kSlab;              // one attention tile or Q tile
+    static constexpr int kQV = NS / 2;                   // 16-byte vectors per thread of a Q tile
     static constexpr int kStageRow = kChanWave * 2 + 16;
     static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kWeightStage = kChanBlock * kRow;
-    static constexpr int kTiles = 2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage;
-    static constexpr int kQV = NS / 2;                   // 16-byte vectors per thread of a Q tile
-    static constexpr int kLds = kTiles + kBuf + kWaves * kStageWave;    // two tiles, the Q tile, staging
+    static constexpr int kTiles = 4 * kBuf;              // two attention tiles (or hi, lo) and two Q tiles
+    static constexpr int kLds = kTiles + kWaves * kStageWave;
+    static_assert(kWeightStage <= kTiles, "the weights are staged through the tile area");
     static_assert(NS % 2 == 0 && TB * 16 == kThreads, "the Q tile copy takes two slabs per pass");
+    static_assert(KCH == 2 * kUnits, "one attention unit per two chunks of matrix instructions");
 };
+
+__device__ __forceinline__ int lds_swizzle(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
 template <class T, int KCH, int IO>
 __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restrict__ q_ms,
@@ -224,6 +239,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     typedef typename Tr::Vec Vec;
     typedef typename Tr::Frag Frag;
     constexpr bool kHiLo = S::kHiLo;
+    constexpr int kUnits = S::kUnits;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const unsigned L = xcd_remap(blockIdx.x, gridDim.x);
@@ -231,15 +247,86 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     const long t_begin = (long)(L / (unsigned)n_cg) * tiles_per_block;
     const long t_end = t_begin + tiles_per_block < n_tt ? t_begin + tiles_per_block : n_tt;
     if (t_begin >= t_end) return;
+    const int n_mine = (int)(t_end - t_begin);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = lane_id(), x16 = lane & 15, q = lane >> 4;
     const int K = n_hb * 16;
     const unsigned row_bytes = (unsigned)K * 2u;
     const int ch0 = cg * S::kChanBlock + wave * S::kChanWave;
 
-    Vec wf[IO][KCH];
+    // tile number -> (image, first token in it), walked with counters: no division in the loop
+    struct Origin {
+        int b, n0;
+    };
+    auto advance = [&](Origin o) {
+        o.n0 += S::TB;
+        if (o.n0 >= N) { o.n0 = 0; ++o.b; }
+        return o;
+    };
+    const Origin first = {(int)(t_begin / tiles_per_image), (int)(t_begin % tiles_per_image) * S::TB};
 
-    // this wave's head-branches: state operands and eps*scale, reloaded when the image changes
+    // ---- Q tile: copied in row order (8 lanes per 128-byte row segment; read as fragments straight
+    // from memory every lane would touch its own row) into LDS.  Rows past the image's last token
+    // and tiles past this workgroup's last read as zero.
+    const int q_slab = threadIdx.x >> 8, q_row = (threadIdx.x >> 3) & 31, q_chunk = threadIdx.x & 7;
+    const int q_lds = q_slab * S::kSlab + q_row * S::kRow + lds_swizzle(q_row, q_chunk) * 16;
+    const unsigned q_glb = q_row * row_bytes + q_slab * 128 + q_chunk * 16;
+    u32x4 qv[S::kQV];
+    BufRsrc qres;
+    auto aim_q = [&](Origin o, bool live) {
+        const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
+        qres = make_rsrc(q_ms + ((long)o.b * N + o.n0) * K, (long)rows * row_bytes);
+    };
+    auto fetch_q1 = [&](int i) {
+        qv[i] = buf_load16(qres, q_slab * 128 + q_chunk * 16 + i * 256 < row_bytes ? q_glb + i * 256 : kOobOffset, 0);
+    };
+    auto park_q1 = [&](char* qb, int i) { *(u32x4*)(qb + q_lds + 2 * i * S::kSlab) = qv[i]; };
+
+    aim_q(first, true);      // requested ahead of the weights, so the first tile does not queue behind them
+#pragma unroll
+    for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
+
+    // ---- weights -> registers, copied in row order through LDS (fragment reads straight from
+    // memory would touch one cache line per lane).  All slabs are requested at once: the registers
+    // they wait in are the ones the fragments move into, and the memory latency is paid once.
+    Vec wf[IO][KCH];
+    const int g16 = (x16 >> 1) & 7;
+    {
+        const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
+        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
+        unsigned base[kWV];
+        int wl[kWV];
+#pragma unroll
+        for (int i = 0; i < kWV; ++i) {
+            const int r = (threadIdx.x + i * S::kThreads) >> 3;
+            const int row = cg * S::kChanBlock + r;
+            base[i] = row < c_out ? (unsigned)row * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
+            wl[i] = r * S::kRow + lds_swizzle(r, threadIdx.x & 7) * 16;
+        }
+        u32x4 wr[S::NS][kWV];
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl)
+#pragma unroll
+            for (int i = 0; i < kWV; ++i)
+                wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
+                                                 ? base[i] + sl * 128 : kOobOffset, 0);
+#pragma unroll
+        for (int sl = 0; sl < S::NS; ++sl) {
+            if (sl) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kWV; ++i) *(u32x4*)(lds + wl[i]) = wr[sl][i];
+            __syncthreads();
+#pragma unroll
+            for (int io = 0; io < IO; ++io)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wf[io][2 * sl + h] = __builtin_bit_cast(
+                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + ((h * 4 + q) ^ g16) * 16));
+        }
+        __syncthreads();
+    }
+
+    // ---- this wave's head-branches: state operands and eps*scale, reloaded when the image changes
     Vec a_kv[S::HBW], a_ks[S::HBW];
     float eps_s[S::HBW];
     int img = -1;
@@ -255,58 +342,31 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         img = b;
     };
 
-    // The Q tile (32 tokens x all head-branches) is copied in row order -- 8 lanes per 128-byte row
-    // segment; read as fragments straight from memory every lane would touch its own row -- into
-    // LDS, laid out like the attention tile.  Rows past the image's last token read as zero.
-    char* qbuf = lds + S::kTiles;
-    u32x4 qv[S::kQV];
-    auto tile_origin = [&](long tile, int& b, int& n0) {
-        b = (int)(tile / tiles_per_image);
-        n0 = (int)(tile % tiles_per_image) * S::TB;
-    };
-    const int q_slab = threadIdx.x >> 8, q_row = (threadIdx.x >> 3) & 31, q_chunk = threadIdx.x & 7;
-    auto fetch_q = [&](long tile) {
-        int b, n0;
-        tile_origin(tile, b, n0);
-        const long tok0 = (long)b * N + n0;
-        const int rows = tile < t_end ? (N - n0 < S::TB ? N - n0 : S::TB) : 0;
-        const BufRsrc qres = make_rsrc(q_ms + tok0 * K, (long)rows * row_bytes);
-#pragma unroll
-        for (int i = 0; i < S::kQV; ++i) {
-            const unsigned col = (2 * i + q_slab) * 128 + q_chunk * 16;
-            qv[i] = buf_load16(qres, col < row_bytes ? q_row * row_bytes + col : kOobOffset, 0);
-        }
-    };
-    auto park_q = [&]() {
-#pragma unroll
-        for (int i = 0; i < S::kQV; ++i)
-            *(u32x4*)(qbuf + (2 * i + q_slab) * S::kSlab + q_row * S::kRow + q_chunk * 16) = qv[i];
-    };
-    // Attention rows of unit u = (jt, j) = 16 tokens x head-branch wave*HBW + j, Q tile -> tile(s) in
-    // LDS, a lane handling channels 4q..4q+3 of its token.  The unit is cut into three stages
-    // (request Q; rectify and issue the two MFMAs; normalise and store) that the callers place in
-    // different slots of their instruction stream, so no stage waits for the one before it.
-    constexpr int kUnits = S::JT * S::HBW;
+    // ---- attention rows of unit u = (jt, j) = 16 tokens x head-branch wave*HBW + j: Q tile ->
+    // attention tile(s), a lane handling channels 4q..4q+3 of its token.  Three stages (request Q;
+    // rectify and issue the two MFMAs; normalise and store) that the callers place in different
+    // slots of their instruction stream, so no stage waits for the one before it.
     Frag att_q[2];
-    f32x4 att_num[2], att_den[2];
+    f32x4 att_num, att_den;
     auto unit_off = [&](int u) {
         const int hb = wave * S::HBW + u % S::HBW;
-        return (hb >> 2) * S::kSlab + ((u / S::HBW) * 16 + x16) * S::kRow + (hb & 3) * 32 + q * 8;
+        const int chunk = (hb & 3) * 2 + (q >> 1);
+        return (hb >> 2) * S::kSlab + ((u / S::HBW) * 16 + x16) * S::kRow + (chunk ^ g16) * 16 + (q & 1) * 8;
     };
-    auto att_a = [&](int u) { att_q[u & 1] = load_frag<T>((const T*)(qbuf + unit_off(u))); };
+    auto att_a = [&](const char* qb, int u) { att_q[u & 1] = load_frag<T>((const T*)(qb + unit_off(u))); };
     auto att_b = [&](int u) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         const Frag qf = frag_relu<T>(att_q[u & 1]);
         Vec b;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { b[r] = qf[r]; b[4 + r] = qf[r]; }   // pairs with {hi, lo} of the state
-        att_num[u & 1] = Tr::mma_vec(z, a_kv[u % S::HBW], b);
-        att_den[u & 1] = Tr::mma_vec(z, a_ks[u % S::HBW], b);
+        att_num = Tr::mma_vec(z, a_kv[u % S::HBW], b);
+        att_den = Tr::mma_vec(z, a_ks[u % S::HBW], b);
     };
     auto att_c = [&](int u, char* hi_tile, char* lo_tile) {
         const int hb = wave * S::HBW + u % S::HBW;
-        const f32x4 num = att_num[u & 1];
-        const float inv = hb < n_hb ? __builtin_amdgcn_rcpf(att_den[u & 1][0] + eps_s[u % S::HBW]) : 0.f;
+        const f32x4 num = att_num;
+        const float inv = hb < n_hb ? __builtin_amdgcn_rcpf(att_den[0] + eps_s[u % S::HBW]) : 0.f;
         const f32x4 o = {num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
         const int off = unit_off(u);
         if constexpr (kHiLo) {
@@ -319,71 +379,35 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         }
     };
     // all units of a tile, the stages of neighbouring units overlapped
-    auto att_all = [&](char* hi_tile, char* lo_tile) {
-        att_a(0);
+    auto att_all = [&](const char* qb, char* hi_tile, char* lo_tile) {
+        att_a(qb, 0);
 #pragma unroll
         for (int u = 0; u < kUnits; ++u) {
-            if (u + 1 < kUnits) att_a(u + 1);
             att_b(u);
-            if (u > 0) att_c(u - 1, hi_tile, lo_tile);
+            if (u + 1 < kUnits) att_a(qb, u + 1);
+            att_c(u, hi_tile, lo_tile);
         }
-        att_c(kUnits - 1, hi_tile, lo_tile);
     };
 
+    // ---- projection: token-operand fragments are requested kAhead chunks ahead of their use (one
+    // where the weights alone take half the register file)
+    constexpr int kAhead = IO * KCH >= 32 ? 1 : 2;
+    constexpr int kRing = kAhead + 1;
     f32x4 acc[IO][S::JT];
-    char* stage = lds + S::kTiles + S::kBuf + wave * S::kStageWave;
-    const int frag_off = x16 * S::kRow + q * 16;
-    // token-operand fragments are requested two contraction chunks ahead of their use
-    Vec bf[3][S::JT];
+    char* stage = lds + S::kTiles + wave * S::kStageWave;
+    const int frag_off = x16 * S::kRow + (q ^ g16) * 16;       // chunk (kk&1)*4 + q: the second half is ^ 64
+    Vec bf[kRing][S::JT];
     auto read_b = [&](const char* tile, int kk) {
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt)
-            bf[kk % 3][jt] = __builtin_bit_cast(
-                Vec, *(const u32x4*)(tile + frag_off + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
+            bf[kk % kRing][jt] = __builtin_bit_cast(
+                Vec, *(const u32x4*)(tile + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
     };
     auto mma_chunk = [&](int kk) {
 #pragma unroll
         for (int io = 0; io < IO; ++io)
 #pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
-    };
-    // Results leave in two steps.  finish() rounds a tile's accumulators into registers; flush()
-    // -- called at the top of the NEXT tile's period, after the wait for that period's Q loads and
-    // before the following loads are requested -- parks them in this wave's staging rows and writes
-    // 16-byte words.  The memory counter is in order, so a wait for loads also waits for every older
-    // store: placed there, the stores have a whole period to complete before anything waits on them.
-    Frag pend[IO][S::JT];
-    auto finish = [&]() {
-#pragma unroll
-        for (int io = 0; io < IO; ++io)
-#pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
-    };
-    auto flush = [&](long tile) {
-        int b, n0;
-        tile_origin(tile, b, n0);
-        const long tok0 = (long)b * N + n0;
-        const int rows = N - n0 < S::TB ? N - n0 : S::TB;
-        const unsigned out_row = (unsigned)c_out * 2u;
-        const BufRsrc ores = make_rsrc(out + tok0 * c_out, (long)rows * out_row);
-#pragma unroll
-        for (int jt = 0; jt < S::JT; ++jt) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int io = 0; io < IO; ++io)
-                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row
-            if (lane < 16 * kVecRow) {
-                const int row = lane / kVecRow, cv = lane % kVecRow;
-                const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
-                const int oc = ch0 + cv * 8;
-                buf_store16(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
-            }
-        }
+            for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[kk % kRing][jt]);
     };
     auto zero_acc = [&]() {
 #pragma unroll
@@ -391,103 +415,142 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
             for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
     };
-    auto image_of = [&](long tile) { return (int)(tile / tiles_per_image); };
 
-    fetch_q(t_begin);      // requested ahead of the weights, so the first tile does not queue behind them
-    // weights -> registers, copied in row order through LDS (see the projection kernel)
-    {
-        const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
-        constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
-        unsigned base[kWV];
+    // ---- results: finish() rounds a tile's accumulators into registers; the two pieces (16 tokens
+    // each) then go through this wave's staging rows -- flush_a parks one, flush_b writes it out as
+    // 16-byte words, whole runs of a token's channels.
+    Frag pend[IO][S::JT];
+    BufRsrc ores;
+    const unsigned out_row = (unsigned)c_out * 2u;
+    auto finish = [&]() {
 #pragma unroll
-        for (int i = 0; i < kWV; ++i) {
-            const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
-            base[i] = row < c_out ? (unsigned)row * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
+        for (int io = 0; io < IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
+    };
+    auto aim_out = [&](Origin o, bool live) {
+        const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
+        ores = make_rsrc(out + ((long)o.b * N + o.n0) * c_out, (long)rows * out_row);
+    };
+    auto flush_a = [&](int jt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int io = 0; io < IO; ++io)
+            store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto flush_b = [&](int jt) {
+        constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row
+        if (lane < 16 * kVecRow) {
+            const int row = lane / kVecRow, cv = lane % kVecRow;
+            const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
+            const int oc = ch0 + cv * 8;
+            buf_store16(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
         }
-        // all slabs are requested at once (the registers they wait in are the ones the fragments
-        // move into), so the memory latency is paid once
-        u32x4 wr[S::NS][kWV];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto flush_all = [&](Origin o) {
+        aim_out(o, true);
 #pragma unroll
-        for (int sl = 0; sl < S::NS; ++sl)
-#pragma unroll
-            for (int i = 0; i < kWV; ++i)
-                wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
-                                                 ? base[i] + sl * 128 : kOobOffset, 0);
-#pragma unroll
-        for (int sl = 0; sl < S::NS; ++sl) {
-            if (sl) __syncthreads();
-#pragma unroll
-            for (int i = 0; i < kWV; ++i)
-                *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl][i];
-            __syncthreads();
-#pragma unroll
-            for (int io = 0; io < IO; ++io)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wf[io][2 * sl + h] = __builtin_bit_cast(
-                        Vec, *(const u32x4*)(lds + (wave * S::kChanWave + io * 16 + x16) * S::kRow + (h * 4 + q) * 16));
+        for (int jt = 0; jt < S::JT; ++jt) {
+            flush_a(jt);
+            flush_b(jt);
         }
-        __syncthreads();
-    }
+    };
 
-    char* tile0 = lds;
-    char* tile1 = lds + S::kBuf;
+    char* att0 = lds;
+    char* att1 = lds + S::kBuf;
+    char* qb0 = lds + 2 * S::kBuf;
+    char* qb1 = lds + 3 * S::kBuf;
     if constexpr (!kHiLo) {
-        // prologue: attention rows of the first tile
-        load_state(image_of(t_begin));
-        park_q();
-        fetch_q(t_begin + 1);
-        __syncthreads();
-        att_all(tile0, nullptr);
-        __syncthreads();
-        int cur = 0;
-        for (long tile = t_begin; tile < t_end; ++tile) {
-            const char* here = cur ? tile1 : tile0;
-            char* next = cur ? tile0 : tile1;
-            if (tile + 1 < t_end && image_of(tile + 1) != img) load_state(image_of(tile + 1));
-            park_q();                  // Q of tile + 1 (zeros past the last tile)
-            if (tile > t_begin) flush(tile - 1);
-            fetch_q(tile + 2);
-            __syncthreads();
-            zero_acc();
-            // The attention rows of the next tile are dealt out between the chunks of this tile's
-            // matrix instructions -- one unit per KCH/kUnits chunks, its three stages in consecutive
-            // slots -- so their latencies and vector arithmetic run in the MFMAs' shadow.  Past the
-            // last tile this makes rows of zeros that nobody reads.
-            constexpr int kPer = KCH / kUnits;
-            static_assert(kPer == 2, "one unit per two chunks");
-            read_b(here, 0);
-            read_b(here, 1);
-            att_a(0);
+        // prologue: Q tiles 0 and 1 parked, Q tile 2 requested, attention rows of tile 0 made
+        Origin o_att = first;                 // tile whose attention rows are made next
+        Origin o_q = advance(first);          // tile whose Q is requested next
 #pragma unroll
-            for (int kk = 0; kk < KCH; ++kk) {
-                if (kk + 2 < KCH) read_b(here, kk + 2);
-                const int u = kk / 2;
-                if (kk % 2 == 0) {
+        for (int i = 0; i < S::kQV; ++i) park_q1(qb0, i);
+        aim_q(o_q, 1 < n_mine);
+#pragma unroll
+        for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
+#pragma unroll
+        for (int i = 0; i < S::kQV; ++i) park_q1(qb1, i);
+        o_q = advance(o_q);
+        aim_q(o_q, 2 < n_mine);
+#pragma unroll
+        for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
+        load_state(o_att.b);
+        __syncthreads();
+        att_all(qb0, att0, nullptr);
+        __syncthreads();
+        Origin o_out = first;                 // tile whose results are written next
+        o_att = advance(o_att);
+        for (int t = 0; t < n_mine; ++t) {
+            const bool odd = t & 1;
+            const char* here = odd ? att1 : att0;       // attention rows of tile t
+            char* next = odd ? att0 : att1;             // ... of tile t+1, made now
+            const char* q_next = odd ? qb0 : qb1;       // Q of tile t+1
+            char* q_park = odd ? qb1 : qb0;             // Q of tile t+2 goes where tile t's was
+            if (t + 1 < n_mine && o_att.b != img) load_state(o_att.b);
+            o_q = advance(o_q);
+            aim_q(o_q, t + 3 < n_mine);                 // resource of Q tile t+3
+            aim_out(o_out, t > 0);                      // ... and of the results of tile t-1 (none before the first)
+            zero_acc();
+            read_b(here, 0);
+            if constexpr (kAhead > 1) read_b(here, 1);
+            att_a(q_next, 0);
+            // 16 slots of IO*2 matrix instructions; everything else rides between them.  Past the
+            // last tile the extra jobs work on zeros that nobody reads.
+            static_for<0, KCH>([&](auto kk_c) {
+                constexpr int kk = decltype(kk_c)::value;
+                if constexpr (kk + kAhead < KCH) read_b(here, kk + kAhead);
+                constexpr int u = kk / 2;
+                if constexpr (kk % 2 == 0) {
                     att_b(u);
-                    if (u + 1 < kUnits) att_a(u + 1);
+                    if constexpr (u + 1 < kUnits) att_a(q_next, u + 1);
                 } else {
                     att_c(u, next, nullptr);
                 }
                 mma_chunk(kk);
+                // Q tile t+2: registers -> LDS, then the same registers take the request for tile t+3
+                constexpr int kParkAt = 1, kFetchAt = 3;
+                if constexpr (kk >= kParkAt && kk < kParkAt + S::kQV) park_q1(q_park, kk - kParkAt);
+                if constexpr (kk >= kFetchAt && kk < kFetchAt + S::kQV) fetch_q1(kk - kFetchAt);
+                // results of tile t-1: two pieces, each parked and written a quarter of the slots later
+                static_assert(kFetchAt + S::kQV <= KCH && S::JT == 2, "slot plan");
+                if constexpr (kk == KCH / 8) flush_a(0);
+                if constexpr (kk == 3 * KCH / 8) flush_b(0);
+                if constexpr (kk == KCH / 2) flush_a(1);
+                if constexpr (kk == 3 * KCH / 4) flush_b(1);
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
             finish();
+            if (t > 0) o_out = advance(o_out);
+            o_att = advance(o_att);
             __syncthreads();
-            cur ^= 1;
         }
-        flush(t_end - 1);
+        flush_all(o_out);
     } else {
-        for (long tile = t_begin; tile < t_end; ++tile) {
-            if (image_of(tile) != img) load_state(image_of(tile));
-            park_q();
-            if (tile > t_begin) flush(tile - 1);
-            fetch_q(tile + 1);
+        Origin o = first, o_q = first, o_out = first;
+        for (int t = 0; t < n_mine; ++t) {
+            if (o.b != img) load_state(o.b);
+#pragma unroll
+            for (int i = 0; i < S::kQV; ++i) park_q1(qb0, i);
+            if (t > 0) {
+                flush_all(o_out);
+                o_out = advance(o_out);
+            }
+            o_q = advance(o_q);
+            aim_q(o_q, t + 1 < n_mine);
+#pragma unroll
+            for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
             __syncthreads();           // Q tile complete; every wave is done with the previous tiles
-            att_all(tile0, tile1);
+            att_all(qb0, att0, att1);
             __syncthreads();
             zero_acc();
-            read_b(tile0, 0);
+            read_b(att0, 0);
 #pragma unroll
             for (int kk = 0; kk < KCH; ++kk) {
                 // the hi fragments come through the ring, one chunk ahead; the lo ones are read here
@@ -495,8 +558,8 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
                 for (int jt = 0; jt < S::JT; ++jt)
                     lo[jt] = __builtin_bit_cast(
-                        Vec, *(const u32x4*)(tile1 + frag_off + (kk >> 1) * S::kSlab + jt * 16 * S::kRow + (kk & 1) * 64));
-                if (kk + 1 < KCH) read_b(tile0, kk + 1);
+                        Vec, *(const u32x4*)(att1 + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
+                if (kk + 1 < KCH) read_b(att0, kk + 1);
                 mma_chunk(kk);
 #pragma unroll
                 for (int io = 0; io < IO; ++io)
@@ -504,8 +567,9 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
                     for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], lo[jt]);
             }
             finish();
+            o = advance(o);
         }
-        flush(t_end - 1);
+        flush_all(o_out);
     }
 }
 
