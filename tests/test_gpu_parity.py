@@ -206,6 +206,23 @@ def test_forward_small(dtype, B, C, H, W, heads, scales):
     check_module(t, dtype, heads, d, scales)
 
 
+@pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
+    ("f16", 4, 128, 64, 64, 8, (5,)),      # 16 head-branches, 128 output channels, two tiles per workgroup
+    ("f16", 8, 128, 33, 35, 8, (3, 5)),    # 24 head-branches, ragged tiles, workgroups that cross images
+    ("bf16", 8, 128, 33, 35, 8, (5,)),     # the hi/lo path over several ragged tiles
+    ("f16", 3, 256, 64, 96, 16, (5,)),     # 32 head-branches, 256 output channels, three tiles per workgroup
+    ("bf16", 2, 256, 64, 128, 16, (5,)),
+    ("f16", 2, 64, 96, 96, 4, ()),         # no aggregated scale: 4 head-branches
+])
+def test_forward_several_tiles_per_workgroup(dtype, B, C, H, W, heads, scales):
+    """Shapes at which the persistent projection and apply workgroups walk over several token
+    tiles each (more than 256 tiles of 32 tokens), in every register-resident-weight variant."""
+    d = 16
+    print(f"forward, several tiles per workgroup: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
+    t = wk.random_module(C * 1000 + B * 100 + H + W, dtype, B, C, H, W, heads, d, scales)
+    check_module(t, dtype, heads, d, scales)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_forward_benchmark_configs_full_size(cfg):
     """The five workload shapes at full size, in the launch configuration the bench times."""
