@@ -308,8 +308,12 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         // MFMA; (3) rectify, pack, store.  Two transposition buffers alternate.
         constexpr int NR = R + 2 * P;
         f32x4 acc[KS];
-        f32x4 s1v[2], s2v[2];             // V after the permutation; MFMA results awaiting stage 3
+        Frag s1v[2][2];                   // V (hi, lo) after the lane permutation
+        f32x4 s2v[2];                     // MFMA results awaiting stage 3
         auto pass_t = [](int pass) { return pass == 0 ? 1 : pass == 1 ? 2 : 0; };     // K, V, Q
+        // A finished row sits as lane (channel blk, x-block sub) = 4 tokens of one channel.  It is
+        // rounded to the operand type first (hi and lo halves for bf16), so everything that moves is
+        // 8 bytes per lane.
         auto stage1 = [&](int it, f32x4 o) {
             const int t = pass_t(it / NR), y = it % NR - (KS - 1);
             const int gy = gy0 + y;
@@ -320,12 +324,23 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 for (int i = 0; i < 4; ++i)
                     if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;
             }
+            Frag hi, lo;
+            if constexpr (Tr::kHiLo) frag_split<T>(o, hi, lo);
+            else hi = frag_from_f32<T>(o);
             if (t == 2) {
                 // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s1v[it & 1][i] = __shfl(o[i], 4 * x16 + q);
+                const u32x2 h2 = __builtin_bit_cast(u32x2, hi);
+                s1v[it & 1][0] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)h2[0], 4 * x16 + q),
+                                                                (unsigned)__shfl((int)h2[1], 4 * x16 + q)});
+                if constexpr (Tr::kHiLo) {
+                    const u32x2 l2 = __builtin_bit_cast(u32x2, lo);
+                    s1v[it & 1][1] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)l2[0], 4 * x16 + q),
+                                                                    (unsigned)__shfl((int)l2[1], 4 * x16 + q)});
+                }
             } else {
-                // K, Q: 16 tokens x 16 channels -> lane (token 4*xblock + i, q) with channels 4q..4q+3
+                // K, Q: the 16 channels x 16 tokens are written as they are -- 8 bytes per lane, in
+                // lane order, a [channel][token] matrix -- and picked up transposed by the LDS
+                // transpose read in stage 2
                 char* tb = trans + (it & 1) * L::kTransBytes;
                 wave_lds_fence();
 #pragma unroll
@@ -333,18 +348,23 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 wave_lds_fence();
             }
         };
+        // ds_read_b64_tr_b16 on lane addresses base + 8*lane: lane (token x16, q) receives channels
+        // 4q..4q+3 of its token out of the [channel][token] matrix written above (within a group of
+        // 16 lanes, lane l gets element l%4 of the 8-byte chunks l/4, l/4 + 4, l/4 + 8, l/4 + 12).
+        auto read_transposed = [&](const char* p) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            typedef __attribute__((address_space(3))) s16x4* LdsPtr;
+            return __builtin_bit_cast(Frag, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsPtr)(p + lane * 8)));
+        };
         auto stage2 = [&](int it) {
             const int t = pass_t(it / NR), y = it % NR - (KS - 1);
             if (t == 2) {
-                const f32x4 vf = s1v[it & 1];
                 if constexpr (Tr::kHiLo) {
-                    Frag vh, vl;
-                    frag_split<T>(vf, vh, vl);
-                    kv_agg = Tr::mma16(kv_agg, aggK[y], vh);
-                    kv_agg = Tr::mma16(kv_agg, aggK[y], vl);
-                    kv_agg = Tr::mma16(kv_agg, aggK_lo[y], vh);
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], s1v[it & 1][0]);
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], s1v[it & 1][1]);
+                    kv_agg = Tr::mma16(kv_agg, aggK_lo[y], s1v[it & 1][0]);
                 } else {
-                    kv_agg = Tr::mma16(kv_agg, aggK[y], frag_from_f32<T>(vf));
+                    kv_agg = Tr::mma16(kv_agg, aggK[y], s1v[it & 1][0]);
                 }
                 return;
             }
