@@ -350,6 +350,8 @@ __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __rest
     float v = 0.f;
     if (j < kStateSize) {
         const float* p = partials + (long)s_id * nchunks * kStateSize + j;
+        // the additions stay in chunk order; unrolling only lets several loads be in flight
+#pragma unroll 8
         for (int c = 0; c < nchunks; ++c) v += p[(long)c * kStateSize];
         st[j] = v;
         kv32[(long)s_id * kStateSize + j] = v;

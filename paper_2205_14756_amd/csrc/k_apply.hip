@@ -28,29 +28,46 @@ using ApplyTile = GemmTile<T, MSLA_APPLY_WR, MSLA_APPLY_WC>;
 // q: channels 4q..4q+3 of this lane's token (raw, not yet rectified).
 // state: the 2048-byte operand block of (image, head-branch).  eps_s = eps * scale.
 template <class T>
-__device__ __forceinline__ f32x4 att_unit(typename Traits<T>::Frag qf, const char* state, float eps_s) {
+struct StateOps {
+    u32x4 kv, ks;       // row operands: the state, and Ksum in every row
+    float eps_s;
+};
+template <class T>
+__device__ __forceinline__ StateOps<T> load_state_ops(const char* kvfrag, const float* kvscale, long sid, float eps,
+                                                      bool live) {
+    StateOps<T> s;
+    s.kv = *(const u32x4*)(kvfrag + sid * 2048 + lane_id() * 16);
+    s.ks = *(const u32x4*)(kvfrag + sid * 2048 + 1024 + lane_id() * 16);
+    s.eps_s = live ? eps * kvscale[sid] : 0.f;
+    return s;
+}
+template <class T>
+__device__ __forceinline__ f32x4 att_unit(typename Traits<T>::Frag qf, const StateOps<T>& st) {
     typedef Traits<T> Tr;
-    const int lane = lane_id();
     const f32x4 z = {0.f, 0.f, 0.f, 0.f};
     qf = frag_relu<T>(qf);
     f32x4 num, den;
     if constexpr (Tr::kSplit) {
         typedef typename Tr::Vec Vec;
-        const Vec a_kv = __builtin_bit_cast(Vec, *(const u32x4*)(state + lane * 16));
-        const Vec a_ks = __builtin_bit_cast(Vec, *(const u32x4*)(state + 1024 + lane * 16));
         Vec b;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { b[r] = qf[r]; b[4 + r] = qf[r]; }   // pairs with {hi, lo}
-        num = Tr::mma_vec(z, a_kv, b);
-        den = Tr::mma_vec(z, a_ks, b);
+        num = Tr::mma_vec(z, __builtin_bit_cast(Vec, st.kv), b);
+        den = Tr::mma_vec(z, __builtin_bit_cast(Vec, st.ks), b);
     } else {
-        const f32x4 a_kv = *(const f32x4*)(state + lane * 16);
-        const f32x4 a_ks = *(const f32x4*)(state + 1024 + lane * 16);
-        num = Tr::mma16(z, a_kv, qf);
-        den = Tr::mma16(z, a_ks, qf);
+        num = Tr::mma16(z, __builtin_bit_cast(f32x4, st.kv), qf);
+        den = Tr::mma16(z, __builtin_bit_cast(f32x4, st.ks), qf);
     }
-    const float inv = 1.0f / (den[0] + eps_s);
+    const float inv = 1.0f / (den[0] + st.eps_s);
     return f32x4{num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
+}
+template <class T>
+__device__ __forceinline__ f32x4 att_unit(typename Traits<T>::Frag qf, const char* state, float eps_s) {
+    StateOps<T> st;
+    st.kv = *(const u32x4*)(state + lane_id() * 16);
+    st.ks = *(const u32x4*)(state + 1024 + lane_id() * 16);
+    st.eps_s = eps_s;
+    return att_unit<T>(qf, st);
 }
 
 // ------------------------------------------------------------------ att only
@@ -130,7 +147,17 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
     G::zero(acc);
     u32x4 rw[G::kVecR];
     Frag qreg[TG][HB];
+    // the state operands of a slab's head-branches are requested one slab ahead, like the weights
+    StateOps<T> st[HB];
+    auto fetch_states = [&](int m) {
+#pragma unroll
+        for (int j = 0; j < HB; ++j) {
+            const bool live = m + j < n_hb;
+            st[j] = load_state_ops<T>(kvfrag, kvscale, sid0 + (live ? m + j : 0), eps, live);
+        }
+    };
     G::load_global(rw, w_proj, oc0, c_out, K, 0, K);
+    fetch_states(0);
 #pragma unroll
     for (int g = 0; g < TG; ++g)
 #pragma unroll
@@ -143,12 +170,10 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
 #pragma unroll
         for (int j = 0; j < HB; ++j) {
             const bool live = m0 + j < n_hb;
-            const char* state = kvfrag + (sid0 + m0 + j) * 2048;
-            const float eps_s = live ? eps * kvscale[sid0 + m0 + j] : 0.f;
 #pragma unroll
             for (int g = 0; g < TG; ++g) {
                 f32x4 o = {0.f, 0.f, 0.f, 0.f};
-                if (live) o = att_unit<T>(qreg[g][j], state, eps_s);
+                if (live) o = att_unit<T>(qreg[g][j], st[j]);
                 const int colb = (j * 16 + q * 4) * (int)sizeof(T);      // byte column inside the 128-byte slab
                 const int off = ((g * kWaves + wave) * 16 + x16) * G::kRow + colb;
                 if constexpr (kHiLo) {
@@ -165,6 +190,7 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
         if (k0 + G::BK < K) {
             G::load_global(rw, w_proj, oc0, c_out, K, k0 + G::BK, K);
             const int m1 = m0 + HB;
+            fetch_states(m1);
 #pragma unroll
             for (int g = 0; g < TG; ++g)
 #pragma unroll

@@ -441,7 +441,7 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
     // one resident workgroup per CU (two LDS buffers of 60 KB); whole channel-block groups per workgroup
     const long cus = (long)compute_units() * MSLA_PROJ_RESIDENT;
     long per = (n_tiles + cus - 1) / cus;
-    per = (per + n_rb - 1) / n_rb * n_rb;
+    if (per > n_rb) per = (per + n_rb - 1) / n_rb * n_rb;     // small problems: spread the tiles instead
     const long nblocks = (n_tiles + per - 1) / per;
     constexpr int kLds = 2 * (G::kLdsR + G::kLdsC);
     const hipError_t e = hipFuncSetAttribute((const void*)project_kernel<T, Epilogue>,
