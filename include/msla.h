@@ -31,7 +31,9 @@
  * scales, S = 1 + A branches (branch 0 is the raw Q/K/V map and is always
  * present; branch a+1 is aggregated with a scales[a] x scales[a] kernel; every
  * aggregated branch reads the raw map).
- *   x      [B, H, W, C]            (MSLA_NHWC: a token is one row of C channels)
+ *   x      [B, H, W, C]            (MSLA_NHWC: a token is one row of C channels), or
+ *          [B, C, H, W]            (MSLA_NCHW; turned into the token-major form by a
+ *                                  transposition pass of its own before the module runs)
  *   w_qkv  [3*Ct, C]               row o = (h*3 + t)*head_dim + e, t = 0:Q 1:K 2:V,
  *                                  so each (head, Q/K/V) pair is one contiguous group
  *                                  of head_dim channels (the 3*heads groups of Section 3.1)
@@ -42,12 +44,12 @@
  *   w_gpw  [A, 3*Ct, head_dim]     grouped 1x1: out channel o, input e of o's own group
  *   w_proj [C, S*Ct]               column m = (s*heads + h)*head_dim + f
  *   att    [B, H, W, S*Ct]         column order as w_proj's columns
- *   out    [B, H, W, C]
+ *   out    [B, H, W, C] or [B, C, H, W], as x
  * No bias, normalisation or activation other than the ReLUs of Eq. (2).
  *
  * Supported: head_dim == 16; scales[a] in {3, 5}; n_scales <= 7;
- * C and Ct multiples of 16; MSLA_NHWC.  Anything else that is otherwise
- * well-formed returns MSLA_ERR_UNSUPPORTED.
+ * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  Anything else that is
+ * otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
  */
 #ifndef MSLA_H_
 #define MSLA_H_

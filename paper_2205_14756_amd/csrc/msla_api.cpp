@@ -190,7 +190,9 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     Shape s;
     msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
     if (st != MSLA_OK) return st;
-    if (C % 16 != 0 || layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
+    if (C % 16 != 0) return MSLA_ERR_UNSUPPORTED;
+    // channel-planar x / out: the result is parked where K|V lived, which must be large enough
+    if (layout == MSLA_NCHW && C > 2 * s.Ct) return MSLA_ERR_UNSUPPORTED;
     const Workspace wo = carve(s, dt);
     if (workspace_bytes < wo.total) return MSLA_ERR_WORKSPACE;
 
@@ -205,8 +207,18 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
         return events == nullptr || hipEventRecord(static_cast<hipEvent_t>(events[i]), hs) == hipSuccess;
     };
     if (!mark(0)) return MSLA_ERR_LAUNCH;
+    // The kernels work token-major.  A channel-planar x is first turned into token-major form in
+    // `out` (free until the last kernel); the token-major result is then parked in the K|V area
+    // (dead after the aggregation pass) and turned back into `out`.
+    const void* x_tok = x;
+    void* out_tok = out;
+    if (layout == MSLA_NCHW) {
+        if (msla::launch_transpose((int)dt, x, out, s.B, C, (int)s.N, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+        x_tok = out;
+        out_tok = kv_raw;
+    }
     // Q/K/V projection; raw Q lands in the branch-0 columns of the multi-scale Q map
-    if (msla::launch_qkv_project((int)dt, x, w_qkv, q_ms, q_ms_ts, kv_raw, s.T, C, s.heads, hs) != hipSuccess)
+    if (msla::launch_qkv_project((int)dt, x_tok, w_qkv, q_ms, q_ms_ts, kv_raw, s.T, C, s.heads, hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (!mark(1)) return MSLA_ERR_LAUNCH;
     // aggregation + Eq. (3) state
@@ -216,7 +228,10 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     if (!mark(3)) return MSLA_ERR_LAUNCH;
     // normalise-and-apply fused with the output projection
     if (msla::launch_apply_project((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale),
-                                   w_proj, out, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
+                                   w_proj, out_tok, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    if (layout == MSLA_NCHW &&
+        msla::launch_transpose((int)dt, out_tok, out, s.B, (int)s.N, C, hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (!mark(4)) return MSLA_ERR_LAUNCH;
     return MSLA_OK;

@@ -59,6 +59,10 @@ hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, co
                                 const void* w_proj, void* out, long n_tokens, int tokens_per_image,
                                 int n_hb, int c_out, float eps, hipStream_t stream);
 
+// dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
+hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
+                            hipStream_t stream);
+
 // Number of compute units of the current device (queried once per process).
 int compute_units();
 

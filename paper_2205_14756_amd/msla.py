@@ -113,9 +113,13 @@ def new_workspace(B, C, H, W, heads, head_dim, scales, dtype, device="cuda") -> 
 
 def msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps=1e-15, out=None,
                  workspace=None, stream=None, layout=MSLA_NHWC):
-    """out = MSLA(x): x [B,H,W,C] -> out [B,H,W,C] (see include/msla.h for every shape)."""
+    """out = MSLA(x): x [B,H,W,C] -> out [B,H,W,C], or [B,C,H,W] both with layout=MSLA_NCHW
+    (see include/msla.h for every shape)."""
     _dev(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace)
-    B, H, W, C = x.shape
+    if layout == MSLA_NCHW:
+        B, C, H, W = x.shape
+    else:
+        B, H, W, C = x.shape
     if out is None:
         out = torch.empty_like(x)
     if workspace is None:
@@ -133,7 +137,10 @@ def msla_forward_profiled(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales
                           events, stream=None, layout=MSLA_NHWC):
     """msla_forward that also records 5 caller-created hipEvent_t handles (ints) between its stages."""
     _dev(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace)
-    B, H, W, C = x.shape
+    if layout == MSLA_NCHW:
+        B, C, H, W = x.shape
+    else:
+        B, H, W, C = x.shape
     sc, ns = _scales(scales)
     ev = (ctypes.c_void_p * 5)(*[ctypes.c_void_p(int(e)) for e in events])
     st = load_library().msla_forward_profiled(_ptr(x), _ptr(w_qkv), _ptr(w_dw), _ptr(w_gpw), _ptr(w_proj),

@@ -104,7 +104,7 @@ def test_forward_rejects_bad_arguments_before_launching(lib):
     assert _fwd(lib, layout=5) == INVALID
     assert _fwd(lib, scales=(2,)) == INVALID
     assert _fwd(lib, H=0) == INVALID
-    assert _fwd(lib, layout=1) == UNSUPPORTED        # NCHW not built
+    assert _fwd(lib, layout=1, C=256) == UNSUPPORTED  # channel-planar needs C <= 2 * heads * head_dim
     assert _fwd(lib, d=32) == UNSUPPORTED
     assert _fwd(lib, scales=(9,)) == UNSUPPORTED
     assert _fwd(lib, ws_bytes=1024) == WORKSPACE

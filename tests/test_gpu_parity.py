@@ -231,6 +231,24 @@ def test_forward_benchmark_configs_full_size(cfg):
     check_module(wk.make_inputs(wl), wl.dtype, wl.heads, wl.head_dim, wl.scales, wl.eps)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("B,C,H,W,heads,scales", [(2, 32, 13, 37, 2, (5,)), (1, 128, 70, 65, 8, (3, 5)), (3, 80, 9, 20, 5, ())])
+def test_forward_channel_planar_layout(dtype, B, C, H, W, heads, scales):
+    """x and out as [B, C, H, W]: bit for bit the token-major result, transposed (the token-major
+    result itself is checked against the oracle above)."""
+    d = 16
+    print(f"forward NCHW {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
+    t = wk.random_module(77 + C + H, dtype, B, C, H, W, heads, d, scales)
+    ref = run_forward(t, dtype, heads, d, scales)
+    x = dev(np.ascontiguousarray(np.transpose(t["x"], (0, 3, 1, 2))), dtype)
+    wdw, wg = weights(t, dtype, scales)
+    out = torch.full_like(x, float("nan"))
+    msla.msla_forward(x, dev(t["w_qkv"], dtype), wdw, wg, dev(t["w_proj"], dtype), heads, d, scales, 1e-15,
+                      out=out, workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype),
+                      layout=msla.MSLA_NCHW)
+    assert np.array_equal(np.transpose(host(out), (0, 2, 3, 1)), ref)
+
+
 def test_zeroed_tokens_give_exact_zero_in_raw_branch():
     # whole tokens of x set to zero: Q = K = V = 0 there, so the raw-branch rows of those
     # tokens are 0 / (0 + eps) = 0 exactly, never NaN
