@@ -406,8 +406,7 @@ template <class T, int KS>
 hipError_t run_aggregate_ks(const AggregateArgs& a, unsigned nblocks, hipStream_t stream) {
     constexpr int kLds = AggLds<T, KS>::kBytes;
     if (kLds > 48 * 1024) {   // above the default dynamic-LDS limit (the CU has 160 KB)
-        const hipError_t e = hipFuncSetAttribute((const void*)aggregate_kernel<T, KS>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        const hipError_t e = allow_dynamic_lds<aggregate_kernel<T, KS>>(kLds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((aggregate_kernel<T, KS>), dim3(nblocks), dim3(kAggThreads), kLds, stream, a);

@@ -491,8 +491,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 template <class T, int KS>
 hipError_t run_ks(const AggregateArgs& a, unsigned nblocks, hipStream_t stream) {
     constexpr int kLds = MLds<KS>::kBytes;
-    const hipError_t e = hipFuncSetAttribute((const void*)aggregate_mfma_kernel<T, KS>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    const hipError_t e = allow_dynamic_lds<aggregate_mfma_kernel<T, KS>>(kLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((aggregate_mfma_kernel<T, KS>), dim3(nblocks), dim3(kThreads), kLds, stream, a);
     return hipGetLastError();

@@ -613,8 +613,7 @@ hipError_t run_apply_project_ws(const void* q_ms, const void* kvfrag, const floa
     const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
     const long tiles_per_block = (n_tt + groups - 1) / groups;
     const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
-    const hipError_t e = hipFuncSetAttribute((const void*)apply_project_ws_kernel<T, KCH, IO>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, S::kLds);
+    const hipError_t e = allow_dynamic_lds<apply_project_ws_kernel<T, KCH, IO>>(S::kLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((apply_project_ws_kernel<T, KCH, IO>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
                        stream, (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb,
@@ -661,8 +660,7 @@ hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* 
     if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
     constexpr int kLds = G::kLdsR + G::kLdsC * (Traits<T>::kHiLo ? 2 : 1);
     if (kLds > 48 * 1024) {   // above the default dynamic-LDS limit (the CU has 160 KB)
-        const hipError_t e = hipFuncSetAttribute((const void*)apply_project_kernel<T>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        const hipError_t e = allow_dynamic_lds<apply_project_kernel<T>>(kLds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((apply_project_kernel<T>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream,

@@ -409,8 +409,7 @@ hipError_t run_project_ws(const void* x, const void* w, long n_tokens, int c_in,
     const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
     const long tiles_per_block = (n_tt + groups - 1) / groups;
     const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
-    const hipError_t e = hipFuncSetAttribute((const void*)project_ws_kernel<T, KCH, Epilogue>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, S::kLds);
+    const hipError_t e = allow_dynamic_lds<project_ws_kernel<T, KCH, Epilogue>>(S::kLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((project_ws_kernel<T, KCH, Epilogue>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
                        stream, (const T*)x, (const T*)w, n_tokens, c_in, c_out, n_cg, n_tt, tiles_per_block, ep);
@@ -444,8 +443,7 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
     if (per > n_rb) per = (per + n_rb - 1) / n_rb * n_rb;     // small problems: spread the tiles instead
     const long nblocks = (n_tiles + per - 1) / per;
     constexpr int kLds = 2 * (G::kLdsR + G::kLdsC);
-    const hipError_t e = hipFuncSetAttribute((const void*)project_kernel<T, Epilogue>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    const hipError_t e = allow_dynamic_lds<project_kernel<T, Epilogue>>(kLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((project_kernel<T, Epilogue>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream,
                        (const T*)x, (const T*)w, n_tokens, c_in, c_out, n_rb, n_tiles, per, ep);

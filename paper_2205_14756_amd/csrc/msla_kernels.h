@@ -63,6 +63,21 @@ hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, co
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);
 
+// Raises a kernel's dynamic-LDS limit (the CU has 160 KB; the default limit is 48 KB).  The attribute
+// sticks to the (kernel, device) pair, so it is set once for each: later launches -- also those
+// recorded into a graph -- make no runtime call besides the launch itself.
+template <auto Kernel>
+inline hipError_t allow_dynamic_lds(int bytes) {
+    static bool done[64] = {};      // benign if two threads race to set an entry
+    int dev = 0;
+    const hipError_t eg = hipGetDevice(&dev);
+    if (eg != hipSuccess) return eg;
+    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+    return e;
+}
+
 // Number of compute units of the current device (queried once per process).
 int compute_units();
 

@@ -249,6 +249,40 @@ def test_forward_channel_planar_layout(dtype, B, C, H, W, heads, scales):
     assert np.array_equal(np.transpose(host(out), (0, 2, 3, 1)), ref)
 
 
+def test_forward_replays_from_a_hip_graph():
+    """The module allocates nothing and records only kernel launches, so it can be captured into a
+    HIP graph: every replay -- with eager work and synchronisations of the program's own between
+    them -- must reproduce the eager result bit for bit."""
+    wl = wk.WORKLOADS[2]
+    t = wk.make_inputs(wl)
+    dtype = wl.dtype
+    x = dev(t["x"], dtype)
+    B, H, W, C = x.shape
+    wdw, wg = weights(t, dtype, wl.scales)
+    wq, wp = dev(t["w_qkv"], dtype), dev(t["w_proj"], dtype)
+    ws = poisoned_workspace(B, C, H, W, wl.heads, wl.head_dim, wl.scales, dtype)
+    eager = torch.full_like(x, float("nan"))
+    msla.msla_forward(x, wq, wdw, wg, wp, wl.heads, wl.head_dim, wl.scales, wl.eps, out=eager, workspace=ws)
+    torch.cuda.synchronize()
+    out = torch.full_like(x, float("nan"))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        msla.msla_forward(x, wq, wdw, wg, wp, wl.heads, wl.head_dim, wl.scales, wl.eps, out=out, workspace=ws,
+                          stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        out.fill_(float("nan"))
+        ws.fill_(0xFF if i % 2 else 0x7F)                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {i} differs from the eager result"
+
+
 def test_zeroed_tokens_give_exact_zero_in_raw_branch():
     # whole tokens of x set to zero: Q = K = V = 0 there, so the raw-branch rows of those
     # tokens are 0 / (0 + eps) = 0 exactly, never NaN
