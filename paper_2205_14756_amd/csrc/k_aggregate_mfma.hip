@@ -84,7 +84,7 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <class T, int KS>
+template <class T, int KS, bool kCopyRawQ>
 __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs a) {
     typedef Traits<T> Tr;
     typedef typename Tr::Frag Frag;
@@ -226,22 +226,33 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             const bool row_interior = ly >= P && ly < P + MTH;
             const long tok_first = img_tok0 + (long)gy * a.W + (tx0 - P);
             char* dst_row = planar + x16 * L::kChanBytes + ly * L::kRowBytes + q * 8;
+            // All nine selection MFMAs of the row are issued before any result is touched, so their
+            // latencies overlap (a conversion right behind its MFMA stalls the wave for the whole pass).
+            f32x4 sq[3], sk[3], sv[3];
+#pragma unroll
+            for (int cg = 0; cg < 3; ++cg) {
+                const Vec kvv = __builtin_bit_cast(Vec, bt.kvr[rr][cg]);
+                sq[cg] = Tr::mma16(z, bt.qf[rr][cg], ident);
+                sk[cg] = Tr::mma_vec(z, kvv, selk);
+                sv[cg] = Tr::mma_vec(z, kvv, selv);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int cg = 0; cg < 3; ++cg) {
                 const int lx0 = cg * 16;
                 const bool writes = cg < 2 || q == 0;       // the third group only has columns 32..35
-                const Frag dq = frag_from_f32<T>(Tr::mma16(z, bt.qf[rr][cg], ident));
-                const Vec kvv = __builtin_bit_cast(Vec, bt.kvr[rr][cg]);
-                const Frag dk = frag_from_f32<T>(Tr::mma_vec(z, kvv, selk));
-                const Frag dv = frag_from_f32<T>(Tr::mma_vec(z, kvv, selv));
+                const Frag dq = frag_from_f32<T>(sq[cg]);
+                const Frag dk = frag_from_f32<T>(sk[cg]);
+                const Frag dv = frag_from_f32<T>(sv[cg]);
                 if (writes) {
                     store_frag<T>(dst_row + lx0 * 2, dq);
                     store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
                     store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
                 }
-                if (a.copy_raw_q && row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW && gy < a.H &&
-                    tx0 - P + lx0 + x16 < a.W)
-                    store_frag<T>(q_ms + (tok_first + lx0 + x16) * q_ms_ts + h * 16 + q * 4, bt.qf[rr][cg]);
+                if constexpr (kCopyRawQ) {
+                    if (row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW && gy < a.H && tx0 - P + lx0 + x16 < a.W)
+                        store_frag<T>(q_ms + (tok_first + lx0 + x16) * q_ms_ts + h * 16 + q * 4, bt.qf[rr][cg]);
+                }
                 if (a.do_raw && row_interior) {
                     // raw branch: tokens of this tile's interior only (each token belongs to one tile)
                     Frag rk = frag_relu_bits<T>(dk);
@@ -491,9 +502,16 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 template <class T, int KS>
 hipError_t run_ks(const AggregateArgs& a, unsigned nblocks, hipStream_t stream) {
     constexpr int kLds = MLds<KS>::kBytes;
-    const hipError_t e = allow_dynamic_lds<aggregate_mfma_kernel<T, KS>>(kLds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((aggregate_mfma_kernel<T, KS>), dim3(nblocks), dim3(kThreads), kLds, stream, a);
+    // the copy of the raw Q tokens into the multi-scale map is compiled in only where it is wanted
+    if (a.copy_raw_q) {
+        const hipError_t e = allow_dynamic_lds<aggregate_mfma_kernel<T, KS, true>>(kLds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((aggregate_mfma_kernel<T, KS, true>), dim3(nblocks), dim3(kThreads), kLds, stream, a);
+    } else {
+        const hipError_t e = allow_dynamic_lds<aggregate_mfma_kernel<T, KS, false>>(kLds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((aggregate_mfma_kernel<T, KS, false>), dim3(nblocks), dim3(kThreads), kLds, stream, a);
+    }
     return hipGetLastError();
 }
 
