@@ -9,6 +9,9 @@
 #define MSLA_PROJ_WC 2
 #endif
 
+#ifndef MSLA_WS_RESIDENT
+#define MSLA_WS_RESIDENT 2
+#endif
 #ifndef MSLA_PROJ_BARRIER_AT
 #define MSLA_PROJ_BARRIER_AT 0
 #endif
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
 template <class T, int KCH>
 struct WsShape {
     static_assert(sizeof(T) == 2 && KCH % 2 == 0, "16-bit elements, whole 128-byte slabs");
-    static constexpr int kWaves = 4, kThreads = 256, kResident = 2;
+    static constexpr int kWaves = 4, kThreads = 256, kResident = MSLA_WS_RESIDENT;
     static constexpr int IO = 3;                         // 16-channel groups per wave
     static constexpr int JT = 2;                         // 16-token groups per tile
     static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
@@ -260,7 +263,7 @@ struct WsShape {
 };
 
 template <class T, int KCH, class Epilogue>
-__global__ __launch_bounds__(256) void project_ws_kernel(const T* __restrict__ x, const T* __restrict__ w,
+__global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                          long n_tokens, int c_in, int c_out, int n_cg,
                                                          long n_tt, long tiles_per_block, Epilogue ep) {
     typedef WsShape<T, KCH> S;
