@@ -50,22 +50,6 @@ struct GemmTile {
         }
     }
 
-    // Same, with the matrix rows given by a map (a permuted order of the weight rows).
-    template <int NV, class RowMap>
-    static __device__ __forceinline__ void load_global_rows(u32x4 (&regs)[NV], const T* __restrict__ base,
-                                                            int row0, int row_limit, long ld, int k0,
-                                                            int k_limit, const RowMap& row_of) {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int v = threadIdx.x + i * kThreads;
-            const int row = row0 + (v >> 3);
-            const int k = k0 + (v & 7) * Tr::kVec;
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (row < row_limit && k < k_limit) val = *(const u32x4*)(base + (long)row_of(row) * ld + k);
-            regs[i] = val;
-        }
-    }
-
     // i-th 16-byte vector of this thread's share of a slab -> LDS
     static __device__ __forceinline__ void store_lds_one(char* lds, u32x4 reg, int i) {
         const int v = threadIdx.x + i * kThreads;

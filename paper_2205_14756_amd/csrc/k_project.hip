@@ -1,6 +1,8 @@
 // 1x1 projections  y[n, o] = sum_c x[n, c] * w[o, c]  (Section 3.1: Q = x W_Q,
 // K = x W_K, V = x W_V; also the stand-alone form of the final projection).
-// A tile is 128 tokens x 256 output channels, computed by 8 waves.
+// Two forms: a tiled one (256 output channels x 128 tokens per workgroup, any contraction length,
+// every storage type) and, for 16-bit types with at most 256 contraction slots, a weight-stationary
+// one that keeps the weights in registers and streams the tokens.
 #include "gemm_tile.h"
 #include "msla_kernels.h"
 
