@@ -198,6 +198,8 @@ def test_multiscale_state_and_core(dtype, B, H, W, heads, scales):
     (1, 16, 1, 1, 1, (5,)),
     (1, 32, 6, 6, 2, ()),
     (1, 272, 17, 40, 17, (5,)),     # more than one output-channel block in the projection
+    (1, 48, 12, 20, 2, (5,)),       # C != heads * head_dim: narrower attention than the module
+    (2, 32, 9, 31, 4, (3,)),        # ... and wider
 ])
 def test_forward_small(dtype, B, C, H, W, heads, scales):
     d = 16
