@@ -53,14 +53,16 @@ struct MLds {
     static constexpr int LH = MTH + 2 * P, LW = MTW + 2 * P;
     static constexpr int kRowBytes = 72;                       // 36 columns, 8-byte aligned
     static constexpr int kChanRaw = LH * kRowBytes;
-    // channel stride = 8 banks mod 32, so the 64 lanes' 8-byte reads (16 channels x 4 x-blocks)
-    // spread evenly over the banks
-    static constexpr int kChanBytes = kChanRaw + ((8 - (kChanRaw / 4) % 32 + 32) % 32) * 4;
+    // The channel stride is an odd number of 8-byte slots (16 slots = all 32 banks).  A staging
+    // write puts 16 channels of one x-block side by side: 16 different slots mod 16.  A sweeping
+    // read covers, per 16 lanes, 4 x-blocks of the channels {g, g+4, g+8, g+12}: their strides are
+    // 0, 4, 8, 12 slots mod 16 (times an odd number), the x-blocks fill the gaps.
+    static constexpr int kChanBytes = kChanRaw + ((kChanRaw / 8) % 2 == 0 ? 8 : 0);
     static constexpr int kPlanarBytes = 48 * kChanBytes;
     static constexpr int kTokStride = 80;                      // transposition buffer: 16 tokens x 16 fp32 (+pad)
     static constexpr int kTransBytes = 16 * kTokStride;
     static constexpr int kBytes = 2 * kPlanarBytes + kSweepWaves * 2 * kTransBytes;   // two tiles in flight; two transposition buffers per sweeping wave
-    static_assert(LW <= 36 && (kChanBytes / 4) % 32 == 8, "LDS layout");
+    static_assert(LW <= 36 && (kChanBytes / 8) % 2 == 1, "LDS layout");
 };
 
 template <class T> struct M4;
@@ -109,13 +111,15 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const int w4 = wave & 3;              // staging wave index
     const int sw = (wave - 4) & (kSweepWaves - 1);   // sweeping wave index
     const int x16 = lane & 15, q = lane >> 4;      // 16x16 MFMA view of the lane
-    const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block (channel), row/column inside it
+    const int blk = lane >> 2, sub = lane & 3;     // 4x4x4 view: block, row/column inside it
+    // block -> channel of the group: 16 consecutive lanes take channels 4 apart (LDS banks, see MLds)
+    const int chn = 4 * (blk & 3) + (blk >> 2);
     char* trans = lds + 2 * L::kPlanarBytes + sw * 2 * L::kTransBytes;
 
     const T* wdw = (const T*)a.w_dw + (long)h * 48 * KS * KS;
     const T* wgp = (const T*)a.w_gpw + (long)h * 48 * 16;
 
-    // Toeplitz operands of the three 16-channel groups: lane (channel blk, output i = sub).  The head's
+    // Toeplitz operands of the three 16-channel groups: lane (channel chn, output i = sub).  The head's
     // 48 x KS x KS filter taps are fetched once, coalesced, into LDS (the tile area is still free);
     // each lane then picks its band entries with branch-free LDS reads (index clamped, value masked).
     {
@@ -134,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const int v = 4 * s + k - sub;
-                    const int idx = (v >= 0 && v < KS) ? ((t * 16 + blk) * KS + u) * KS + v : 48 * KS * KS;
+                    const int idx = (v >= 0 && v < KS) ? ((t * 16 + chn) * KS + u) * KS + v : 48 * KS * KS;
                     toep[t][u][s][k] = ((const T*)lds)[idx];
                 }
     __syncthreads();   // the tap table sits where the first tile will be staged
@@ -322,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         Frag s1v[2][2];                   // V (hi, lo) after the lane permutation
         f32x4 s2v[2];                     // MFMA results awaiting stage 3
         auto pass_t = [](int pass) { return pass == 0 ? 1 : pass == 1 ? 2 : 0; };     // K, V, Q
-        // A finished row sits as lane (channel blk, x-block sub) = 4 tokens of one channel.  It is
+        // A finished row sits as lane (channel chn, x-block sub) = 4 tokens of one channel.  It is
         // rounded to the operand type first (hi and lo halves for bf16), so everything that moves is
         // 8 bytes per lane.
         auto stage1 = [&](int it, f32x4 o) {
@@ -339,14 +343,16 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             if constexpr (Tr::kHiLo) frag_split<T>(o, hi, lo);
             else hi = frag_from_f32<T>(o);
             if (t == 2) {
-                // V: lane (channel c, q) <- lane 4c + q: tokens (x-block q, i), the K operand's order
+                // V: lane (channel c, q) <- the lane that swept channel c, x-block q: tokens (x-block q, i),
+                // the K operand's order
+                const int from = 4 * (4 * (x16 & 3) + (x16 >> 2)) + q;
                 const u32x2 h2 = __builtin_bit_cast(u32x2, hi);
-                s1v[it & 1][0] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)h2[0], 4 * x16 + q),
-                                                                (unsigned)__shfl((int)h2[1], 4 * x16 + q)});
+                s1v[it & 1][0] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)h2[0], from),
+                                                                (unsigned)__shfl((int)h2[1], from)});
                 if constexpr (Tr::kHiLo) {
                     const u32x2 l2 = __builtin_bit_cast(u32x2, lo);
-                    s1v[it & 1][1] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)l2[0], 4 * x16 + q),
-                                                                    (unsigned)__shfl((int)l2[1], 4 * x16 + q)});
+                    s1v[it & 1][1] = __builtin_bit_cast(Frag, u32x2{(unsigned)__shfl((int)l2[0], from),
+                                                                    (unsigned)__shfl((int)l2[1], from)});
                 }
             } else {
                 // K, Q: the 16 channels x 16 tokens are written as they are -- 8 bytes per lane, in
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 char* tb = trans + (it & 1) * L::kTransBytes;
                 wave_lds_fence();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) *(float*)(tb + (4 * sub + i) * L::kTokStride + blk * 4) = o[i];
+                for (int i = 0; i < 4; ++i) *(float*)(tb + (4 * sub + i) * L::kTokStride + chn * 4) = o[i];
                 wave_lds_fence();
             }
         };
@@ -367,7 +373,13 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             typedef __attribute__((address_space(3))) s16x4* LdsPtr;
             return __builtin_bit_cast(Frag, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsPtr)(p + lane * 8)));
         };
-        auto stage2 = [&](int it) {
+        // Stage 2 is split: the transposed row is requested from LDS at the top of an iteration and
+        // used after the iteration's depthwise MFMAs, which cover the LDS latency.
+        auto stage2_read = [&](int it) {
+            const char* tb = trans + (it & 1) * L::kTransBytes;
+            return *(const f32x4*)(tb + x16 * L::kTokStride + q * 16);
+        };
+        auto stage2 = [&](int it, f32x4 tq) {
             const int t = pass_t(it / NR), y = it % NR - (KS - 1);
             if (t == 2) {
                 if constexpr (Tr::kHiLo) {
@@ -379,8 +391,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 }
                 return;
             }
-            const char* tb = trans + (it & 1) * L::kTransBytes;
-            const f32x4 tq = *(const f32x4*)(tb + x16 * L::kTokStride + q * 16);
             Frag dwf, dwf_lo;
             if constexpr (Tr::kHiLo) frag_split<T>(tq, dwf, dwf_lo);
             else dwf = frag_from_f32<T>(tq);
@@ -410,32 +420,44 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                                   frag_from_f32<T>(s2v[it & 1]));
             }
         };
+        // input row i of the flat sequence: 8 columns (two k-steps) of this lane's channel and x-block
+        Frag din[2][2];
+        auto fetch_row = [&](int i, Frag (&d)[2]) {
+            const int t = pass_t(i / NR), r = i % NR;
+            const char* src = planar + (t * 16 + chn) * L::kChanBytes + (R * part + r) * L::kRowBytes + col0 * 2;
+            d[0] = load_frag<T>(src);
+            d[1] = load_frag<T>(src + 8);
+        };
+        fetch_row(0, din[0]);
         static_for<0, 3 * NR + 2>([&](auto it_c) {
             constexpr int it = decltype(it_c)::value;
+            // iteration i finishes an output row iff it is the KS-th or a later input row of its pass
+            constexpr auto has_row = [](int i) { return i >= 0 && i < 3 * NR && i % NR >= KS - 1; };
+            constexpr bool kPickUp = has_row(it - 1) && ((it - 1) / NR != 1);     // K or Q row in the transposition buffer
+            // LDS requests first: the next input row and the row handed over one iteration ago
+            if constexpr (it + 1 < 3 * NR) fetch_row(it + 1, din[(it + 1) & 1]);
+            f32x4 tq = z;
+            if constexpr (kPickUp) tq = stage2_read(it - 1);
+            __builtin_amdgcn_sched_barrier(0);
             if constexpr (it < 3 * NR) {
                 const int pass = it / NR, r = it % NR;
                 const int t = pass_t(pass);
-                const char* src = planar + (t * 16 + blk) * L::kChanBytes + (R * part) * L::kRowBytes + col0 * 2;
                 if (r == 0) {
 #pragma unroll
                     for (int i = 0; i < KS; ++i) acc[i] = z;
                 }
-                const Frag d0 = load_frag<T>(src + r * L::kRowBytes);
-                const Frag d1 = load_frag<T>(src + r * L::kRowBytes + 8);
 #pragma unroll
                 for (int u = 0; u < KS; ++u) {
                     const int y = r - u;
                     if (y < 0 || y >= R) continue;
-                    acc[y % KS] = M4<T>::mma(toep[t][u][0], d0, acc[y % KS]);
-                    acc[y % KS] = M4<T>::mma(toep[t][u][1], d1, acc[y % KS]);
+                    acc[y % KS] = M4<T>::mma(toep[t][u][0], din[it & 1][0], acc[y % KS]);
+                    acc[y % KS] = M4<T>::mma(toep[t][u][1], din[it & 1][1], acc[y % KS]);
                 }
             }
-            // iteration i finishes an output row iff it is the KS-th or a later input row of its pass
-            constexpr auto has_row = [](int i) { return i >= 0 && i < 3 * NR && i % NR >= KS - 1; };
-            if constexpr (has_row(it - 1)) stage2(it - 1);
+            if constexpr (has_row(it - 1)) stage2(it - 1, tq);
             if constexpr (has_row(it - 2)) stage3(it - 2);
             if constexpr (has_row(it)) {
-                // output row y of 16 channels x 16 tokens is complete: lane (channel blk, x-block sub)
+                // output row y of 16 channels x 16 tokens is complete: lane (channel chn, x-block sub)
                 // holds the 4 tokens gx0..gx0+3 of image row gy0 + y
                 const int y = it % NR - (KS - 1);
                 const f32x4 o = acc[y % KS];
