@@ -35,6 +35,8 @@
 // K and Q are transposed through a small per-wave LDS buffer into the operand
 // layout of the grouped 1x1 (one 16x16x16 MFMA per 16 tokens), K's result being
 // the row operand of KV, Q's (transposed product) going to HBM.
+#include <algorithm>
+
 #include "msla_device.h"
 #include "msla_kernels.h"
 
@@ -119,32 +121,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const T* wdw = (const T*)a.w_dw + (long)h * 48 * KS * KS;
     const T* wgp = (const T*)a.w_gpw + (long)h * 48 * 16;
 
-    // Toeplitz operands of the three 16-channel groups: lane (channel chn, output i = sub).  The head's
-    // 48 x KS x KS filter taps are fetched once, coalesced, into LDS (the tile area is still free);
-    // each lane then picks its band entries with branch-free LDS reads (index clamped, value masked).
-    {
-        T* wl = (T*)lds;
-        for (int i = threadIdx.x; i < 48 * KS * KS; i += kThreads) wl[i] = wdw[i];
-        if (threadIdx.x == 0) wl[48 * KS * KS] = Tr::from_f32(0.f);     // the entry read by masked-out slots
-    }
-    __syncthreads();
-    Frag toep[3][KS][NS];
-#pragma unroll
-    for (int t = 0; t < 3; ++t)
-#pragma unroll
-        for (int u = 0; u < KS; ++u)
-#pragma unroll
-            for (int s = 0; s < NS; ++s)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int v = 4 * s + k - sub;
-                    const int idx = (v >= 0 && v < KS) ? ((t * 16 + chn) * KS + u) * KS + v : 48 * KS * KS;
-                    toep[t][u][s][k] = ((const T*)lds)[idx];
-                }
-    __syncthreads();   // the tap table sits where the first tile will be staged
-    // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
-    const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
-    const Frag gpw_k = load_frag<T>(wgp + (1 * 16 + x16) * 16 + q * 4);
     // selection matrices for staging: ident picks channel x16 out of 16; selk / selv pick it out of
     // the 32 contraction slots {K 0..15, V 0..15} of a 16-byte K|V load
     Frag ident;
@@ -178,9 +154,18 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const int tile_end = min(n_tiles, tile_begin + a.tiles_per_chunk);
 
     const int strip = sw & 1, part = sw >> 1;     // 16-column strip, group of kSweepRows rows
-    // lane part of the staging load addresses: token x16 of a 16-column group, channels of q
-    const long lane_q_off = (long)x16 * a.q_ts + q * 4;
-    const long lane_k_off = (long)x16 * a.k_ts + q * 8;
+    // The image's maps are addressed through buffer resources with 32-bit byte offsets (the host
+    // checks that an image's map fits); a lane outside the image gets an offset beyond any resource,
+    // so its load returns zero and its store is dropped -- no per-lane branches.
+    const unsigned q_tb = (unsigned)(a.q_ts * sizeof(T)), k_tb = (unsigned)(a.k_ts * sizeof(T));
+    const unsigned q_ms_tb = (unsigned)(q_ms_ts * sizeof(T));
+    const BufRsrc rq = make_rsrc(qmap + img_tok0 * a.q_ts, ((N - 1) * a.q_ts + 16) * (long)sizeof(T));
+    const BufRsrc rk = make_rsrc(kmap + img_tok0 * a.k_ts, ((N - 1) * a.k_ts + 32) * (long)sizeof(T));
+    const BufRsrc rout = make_rsrc(q_ms + img_tok0 * q_ms_ts + (long)a.branch * Ct + h * 16,
+                                   ((N - 1) * q_ms_ts + 16) * (long)sizeof(T));
+    // lane part of the staging load offsets: token x16 of a 16-column group, channels of q
+    const unsigned lane_q_off = x16 * q_tb + q * 4 * (unsigned)sizeof(T);
+    const unsigned lane_k_off = x16 * k_tb + q * 8 * (unsigned)sizeof(T);
 
     // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way.
     // Halo rows are dealt to the waves round-robin and handled two at a time ("batch": 12 loads).
@@ -195,27 +180,22 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     constexpr int kBatches = ((L::LH + 3) / 4 + 1) / 2;
     static_assert(kBatches == 3, "staging schedule below assumes 3 batches per tile");
 
-    auto issue = [&](int tile_id, int it, Batch& bt) {   // staging waves
+    auto issue = [&](int tile_id, int it, Batch& bt, bool live) {   // staging waves; !live: every lane masked
         const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             const int ly = w4 + 4 * (it + rr);
             const int gy = ty0 - P + ly;
-            const bool row_ok = ly < L::LH && gy >= 0 && gy < a.H;
-            // wave-uniform row bases; the lane part of the address is loop-invariant
-            const long tok_first = img_tok0 + (long)gy * a.W + (tx0 - P);
-            const T* qrow = qmap + tok_first * a.q_ts;
-            const T* krow = kmap + tok_first * a.k_ts;
+            const bool row_ok = live && ly < L::LH && gy >= 0 && gy < a.H;
+            // wave-uniform row offset (it may wrap below zero for lanes that are masked anyway)
+            const unsigned tok_first = (unsigned)(gy * a.W + (tx0 - P));
+            const unsigned qrow = tok_first * q_tb + lane_q_off, krow = tok_first * k_tb + lane_k_off;
 #pragma unroll
             for (int cg = 0; cg < 3; ++cg) {
-                const int lx = cg * 16 + x16;
-                const int gx = tx0 - P + lx;
-                bt.qf[rr][cg] = frag_zero<T>();
-                bt.kvr[rr][cg] = u32x4{0u, 0u, 0u, 0u};
-                if (row_ok && gx >= 0 && gx < a.W && lx < L::LW) {
-                    bt.qf[rr][cg] = load_frag<T>(qrow + (cg * 16) * a.q_ts + lane_q_off);
-                    bt.kvr[rr][cg] = *(const u32x4*)(krow + (cg * 16) * a.k_ts + lane_k_off);
-                }
+                const int lx = cg * 16 + x16, gx = tx0 - P + lx;
+                const bool ok = row_ok && gx >= 0 && gx < a.W && lx < L::LW;
+                bt.qf[rr][cg] = __builtin_bit_cast(Frag, buf_load8(rq, ok ? qrow + cg * 16 * q_tb : kOobOffset));
+                bt.kvr[rr][cg] = buf_load16(rk, ok ? krow + cg * 16 * k_tb : kOobOffset, 0);
             }
         }
     };
@@ -283,28 +263,70 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // The two roles run separate loops with the same number of barriers (n_my_tiles + 1), so that
     // the register allocator does not have to keep one role's state alive for the other.
     const int n_my_tiles = tile_end - tile_begin;
+    // The staging waves request the first tile before anything else, so those loads are in flight
+    // while the filter taps travel to LDS.  In the loop no branch surrounds a load: past the last
+    // tile the requests are still made, with every lane masked.  The counter of outstanding loads
+    // then has the same history on every path, and a batch is waited for with the two younger
+    // batches still in flight (the scheduler must not mix the three batches here either: entering
+    // the loop with batch 0 requested last would make every wait in the loop cover the youngest
+    // loads as well).
+    // The head's 48 x KS x KS filter taps are fetched once, coalesced, into LDS -- into the sweeping
+    // waves' transposition buffers, which are idle until the first sweep, so the staging waves can
+    // fill the first tile buffer meanwhile.  (Both roles call this, each on its own path.)
+    auto stage_taps = [&]() {
+        T* wl = (T*)(lds + 2 * L::kPlanarBytes);
+        static_assert((48 * KS * KS + 1) * sizeof(T) <= kSweepWaves * 2 * L::kTransBytes, "tap table");
+        for (int i = threadIdx.x; i < 48 * KS * KS; i += kThreads) wl[i] = wdw[i];
+        if (threadIdx.x == 0) wl[48 * KS * KS] = Tr::from_f32(0.f);     // the entry read by masked-out slots
+        __syncthreads();
+    };
     if (role == 0) {
         Batch ring0, ring1, ring2;
-        if (n_my_tiles > 0) {
-            issue(tile_begin, 0, ring0);
-            issue(tile_begin, 2, ring1);
-            issue(tile_begin, 4, ring2);
-        }
-        for (int step = -1; step < n_my_tiles; ++step) {
-            if (step + 1 < n_my_tiles) {
-                const int tile_id = tile_begin + step + 1;
-                const bool more = step + 2 < n_my_tiles;
-                char* planar = lds + ((step + 1) & 1) * L::kPlanarBytes;
-                consume(tile_id, 0, ring0, planar);
-                if (more) issue(tile_id + 1, 0, ring0);
-                consume(tile_id, 2, ring1, planar);
-                if (more) issue(tile_id + 1, 2, ring1);
-                consume(tile_id, 4, ring2, planar);
-                if (more) issue(tile_id + 1, 4, ring2);
-            }
+        issue(tile_begin, 0, ring0, n_my_tiles > 0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(tile_begin, 2, ring1, n_my_tiles > 0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(tile_begin, 4, ring2, n_my_tiles > 0);
+        __builtin_amdgcn_sched_barrier(0);
+        stage_taps();
+        for (int i = 0; i < n_my_tiles; ++i) {
+            const int tile_id = tile_begin + i;
+            const bool more = i + 1 < n_my_tiles;
+            char* planar = lds + (i & 1) * L::kPlanarBytes;
+            consume(tile_id, 0, ring0, planar);
+            issue(tile_id + 1, 0, ring0, more);
+            consume(tile_id, 2, ring1, planar);
+            issue(tile_id + 1, 2, ring1, more);
+            consume(tile_id, 4, ring2, planar);
+            issue(tile_id + 1, 4, ring2, more);
             __syncthreads();
         }
+        __syncthreads();
     } else {
+    // Toeplitz operands of the three 16-channel groups: lane (channel chn, output i = sub); each lane
+    // picks its band entries with branch-free LDS reads (index clamped, value masked).  Every
+    // sweeping wave is through with the table before the first step's barrier, i.e. before any of
+    // them writes a transposition buffer.
+    stage_taps();
+    Frag toep[3][KS][NS];
+    {
+        const T* wl = (const T*)(lds + 2 * L::kPlanarBytes);
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int u = 0; u < KS; ++u)
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int v = 4 * s + k - sub;
+                        const int idx = (v >= 0 && v < KS) ? ((t * 16 + chn) * KS + u) * KS + v : 48 * KS * KS;
+                        toep[t][u][s][k] = wl[idx];
+                    }
+    }
+    // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
+    const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
+    const Frag gpw_k = load_frag<T>(wgp + (1 * 16 + x16) * 16 + q * 4);
     for (int step = -1; step < n_my_tiles; ++step) {
         if (step >= 0) {
         const int tile_id = tile_begin + step;
@@ -415,9 +437,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3
                 const int gy = gy0 + y;
                 const int gx = tx0 + 16 * strip + x16;
-                if (gy < a.H && gx < a.W)
-                    store_frag<T>(q_ms + (img_tok0 + (long)gy * a.W + gx) * q_ms_ts + (long)a.branch * Ct + h * 16 + q * 4,
-                                  frag_from_f32<T>(s2v[it & 1]));
+                const unsigned off = (unsigned)(gy * a.W + gx) * q_ms_tb + q * 4 * (unsigned)sizeof(T);
+                buf_store8(rout, gy < a.H && gx < a.W ? off : kOobOffset,
+                           __builtin_bit_cast(u32x2, frag_from_f32<T>(s2v[it & 1])));
             }
         };
         // input row i of the flat sequence: 8 columns (two k-steps) of this lane's channel and x-block
@@ -544,6 +566,9 @@ hipError_t run(const AggregateArgs& a, hipStream_t stream) {
     // the kernel reads K and V of a token as one 32-channel run
     if ((const char*)a.v != (const char*)a.k + 16 * sizeof(T) || a.v_ts != a.k_ts || a.v_hs != a.k_hs)
         return hipErrorInvalidValue;
+    // 32-bit byte offsets inside one image's maps
+    const long widest = std::max(std::max(a.q_ts, a.k_ts), (long)a.S * a.heads * 16);
+    if ((long)a.H * a.W * widest * (long)sizeof(T) > 0x7fffffffL) return hipErrorNotSupported;
     if (a.ks == 3) return run_ks<T, 3>(a, (unsigned)nblocks, stream);
     if (a.ks == 5) return run_ks<T, 5>(a, (unsigned)nblocks, stream);
     return hipErrorInvalidValue;

@@ -120,8 +120,10 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
         a.branch = i + 1;
         a.do_raw = (i == 0);
         a.copy_raw_q = (i == 0) ? copy_raw_q : 0;
-        const hipError_t e_launch = (dt == MSLA_F32) ? msla::launch_aggregate((int)dt, a, stream)
-                                                     : msla::launch_aggregate_mfma((int)dt, a, stream);
+        hipError_t e_launch = (dt == MSLA_F32) ? msla::launch_aggregate((int)dt, a, stream)
+                                               : msla::launch_aggregate_mfma((int)dt, a, stream);
+        // an image whose maps exceed the matrix-core kernel's 32-bit offsets takes the general kernel
+        if (e_launch == hipErrorNotSupported) e_launch = msla::launch_aggregate((int)dt, a, stream);
         if (e_launch != hipSuccess) return MSLA_ERR_LAUNCH;
     }
     if (event_before_finalize &&

@@ -218,6 +218,12 @@ __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, unsigned voffset, int sof
 __device__ __forceinline__ void buf_store16(BufRsrc r, unsigned voffset, u32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, 0, 0);
 }
+__device__ __forceinline__ u32x2 buf_load8(BufRsrc r, unsigned voffset) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voffset, 0, 0);
+}
+__device__ __forceinline__ void buf_store8(BufRsrc r, unsigned voffset, u32x2 v) {
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voffset, 0, 0);
+}
 
 
 // Workgroup id -> logical id so that consecutive logical ids run on the same

@@ -37,7 +37,8 @@ struct AggregateArgs {
 hipError_t launch_aggregate(int dt, const AggregateArgs& a, hipStream_t stream);
 
 // Same contract for the 16-bit storage types, depthwise convolution on the matrix cores
-// (16 x 32-token tiles; needs v == k + 16 elements with equal strides).
+// (16 x 32-token tiles; needs v == k + 16 elements with equal strides).  Returns
+// hipErrorNotSupported without launching when one image's maps span 2^31 bytes or more.
 hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream);
 
 // Raw-branch-only variant for n_scales == 0 (no convolution): state of branch 0, optional Q copy.
