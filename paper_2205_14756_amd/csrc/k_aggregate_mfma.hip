@@ -270,16 +270,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // batches still in flight (the scheduler must not mix the three batches here either: entering
     // the loop with batch 0 requested last would make every wait in the loop cover the youngest
     // loads as well).
-    // The head's 48 x KS x KS filter taps are fetched once, coalesced, into LDS -- into the sweeping
-    // waves' transposition buffers, which are idle until the first sweep, so the staging waves can
-    // fill the first tile buffer meanwhile.  (Both roles call this, each on its own path.)
-    auto stage_taps = [&]() {
-        T* wl = (T*)(lds + 2 * L::kPlanarBytes);
-        static_assert((48 * KS * KS + 1) * sizeof(T) <= kSweepWaves * 2 * L::kTransBytes, "tap table");
-        for (int i = threadIdx.x; i < 48 * KS * KS; i += kThreads) wl[i] = wdw[i];
-        if (threadIdx.x == 0) wl[48 * KS * KS] = Tr::from_f32(0.f);     // the entry read by masked-out slots
-        __syncthreads();
-    };
     if (role == 0) {
         Batch ring0, ring1, ring2;
         issue(tile_begin, 0, ring0, n_my_tiles > 0);
@@ -288,7 +278,6 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         __builtin_amdgcn_sched_barrier(0);
         issue(tile_begin, 4, ring2, n_my_tiles > 0);
         __builtin_amdgcn_sched_barrier(0);
-        stage_taps();
         for (int i = 0; i < n_my_tiles; ++i) {
             const int tile_id = tile_begin + i;
             const bool more = i + 1 < n_my_tiles;
@@ -303,14 +292,27 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         }
         __syncthreads();
     } else {
-    // Toeplitz operands of the three 16-channel groups: lane (channel chn, output i = sub); each lane
-    // picks its band entries with branch-free LDS reads (index clamped, value masked).  Every
-    // sweeping wave is through with the table before the first step's barrier, i.e. before any of
-    // them writes a transposition buffer.
-    stage_taps();
+    // Toeplitz operands of the three 16-channel groups: lane (channel chn, output i = sub).  Each
+    // sweeping wave copies the head's 48 x KS x KS filter taps, coalesced, into its own transposition
+    // buffers (idle until its first sweep) and picks its band entries from there with branch-free
+    // LDS reads (index clamped, value masked).  Nothing here involves another wave, so the staging
+    // waves fill the first tile buffer meanwhile without a workgroup barrier.
     Frag toep[3][KS][NS];
     {
-        const T* wl = (const T*)(lds + 2 * L::kPlanarBytes);
+        constexpr int kTaps = 48 * KS * KS;
+        static_assert((kTaps + 1) * sizeof(T) <= 2 * L::kTransBytes, "tap table");
+        constexpr int kVecs = kTaps * (int)sizeof(T) / 16;      // 16-byte pieces: a head's taps are a multiple
+        static_assert(kVecs * 16 == kTaps * (int)sizeof(T), "tap table in 16-byte pieces");
+        T* wl = (T*)trans;
+        u32x4 piece[(kVecs + 63) / 64];
+#pragma unroll
+        for (int j = 0; j < (kVecs + 63) / 64; ++j)
+            if (j * 64 + lane < kVecs) piece[j] = ((const u32x4*)wdw)[j * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < (kVecs + 63) / 64; ++j)
+            if (j * 64 + lane < kVecs) ((u32x4*)wl)[j * 64 + lane] = piece[j];
+        if (lane == 0) wl[kTaps] = Tr::from_f32(0.f);     // the entry read by masked-out slots
+        wave_lds_fence();
 #pragma unroll
         for (int t = 0; t < 3; ++t)
 #pragma unroll
@@ -320,9 +322,10 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const int v = 4 * s + k - sub;
-                        const int idx = (v >= 0 && v < KS) ? ((t * 16 + chn) * KS + u) * KS + v : 48 * KS * KS;
+                        const int idx = (v >= 0 && v < KS) ? ((t * 16 + chn) * KS + u) * KS + v : kTaps;
                         toep[t][u][s][k] = wl[idx];
                     }
+        wave_lds_fence();
     }
     // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
     const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
