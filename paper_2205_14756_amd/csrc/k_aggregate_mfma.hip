@@ -45,7 +45,7 @@ namespace {
 
 constexpr int MTH = kAggMfmaTileH;   // 16 tile rows: two halves of 8, one per wave pair
 constexpr int MTW = kAggMfmaTileW;   // 32 tile columns: two 16-token strips
-constexpr int kSweepWaves = 4;       // 4 or 8: each sweeps a 16-column strip x 8 or 4 rows
+constexpr int kSweepWaves = 8;       // 4 or 8: each sweeps a 16-column strip x 8 or 4 rows
 constexpr int kThreads = (4 + kSweepWaves) * 64;     // 4 staging waves + the sweeping waves
 constexpr int kSweepRows = MTH / (kSweepWaves / 2);
 
