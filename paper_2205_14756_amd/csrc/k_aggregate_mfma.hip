@@ -340,6 +340,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         const int col0 = 16 * strip + 4 * sub;            // interior column of this lane's x-block
         const int gy0 = ty0 + R * part;
         const int gx0 = tx0 + col0;
+        const bool ragged = ty0 + MTH > a.H || tx0 + MTW > a.W;      // wave-uniform
         Frag aggK[R], aggK_lo[R];
         // The three passes (K, V, Q) form one flat, fully unrolled sequence of input rows.  A finished
         // output row goes through three stages in three consecutive iterations, so that no stage
@@ -357,9 +358,10 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         auto stage1 = [&](int it, f32x4 o) {
             const int t = pass_t(it / NR), y = it % NR - (KS - 1);
             const int gy = gy0 + y;
-            if (t == 1) {
+            if (t == 1 && ragged) {
                 // tokens outside the image contribute nothing: their aggregated K is made 0, which
-                // also removes their V from the state; Q rows of such tokens are simply not stored
+                // also removes their V from the state; Q rows of such tokens are simply not stored.
+                // (Only a tile that sticks out of the image has such tokens.)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (gy >= a.H || gx0 + i >= a.W) o[i] = 0.f;
