@@ -341,6 +341,52 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
     char* stage = lds + S::kLds - (S::kWaves - wave) * S::kStageWave;
     const char* frag_base = lds + x16 * S::kRow + q * 16;
 
+    // Results leave one tile late: a tile's accumulators are rounded into `pend`, and during the
+    // NEXT tile's matrix instructions they go 16 tokens x 48 channels at a time through this wave's
+    // staging rows (w), come back as 16-byte words covering whole runs of a token's channels (r) and
+    // are stored (s) -- six small jobs dealt out over the contraction chunks, so the wave issues
+    // matrix instructions all the while.  Before the first tile `dest` is an empty resource.
+    typedef typename Traits<T>::Frag Frag;
+    Frag pend[S::IO][S::JT];
+#pragma unroll
+    for (int io = 0; io < S::IO; ++io)
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_zero<T>();
+    auto dest = ep.tile(n_tokens);
+    constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row: 6
+    u32x4 held[2];
+    auto flush_w = [&](int jt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int io = 0; io < S::IO; ++io)
+            store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto flush_r = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int v = lane + 64 * i;
+            if (v < 16 * kVecRow) held[i] = *(const u32x4*)(stage + (v / kVecRow) * S::kStageRow + (v % kVecRow) * 16);
+        }
+    };
+    auto flush_s = [&](int jt) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int v = lane + 64 * i;
+            if (v < 16 * kVecRow)
+                dest.store(ch0, ch0 + S::kChanWave, jt * 16 + v / kVecRow, ch0 + (v % kVecRow) * 8, held[i]);
+        }
+    };
+    auto flush_job = [&](int job) {       // w0 r0 s0 w1 r1 s1
+        if (job % 3 == 0) flush_w(job / 3);
+        else if (job % 3 == 1) flush_r();
+        else flush_s(job / 3);
+    };
+    static_assert(S::JT == 2, "six flush jobs");
+
     park(lds);
     __syncthreads();
     int cur = 0;
@@ -361,44 +407,32 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
         };
         read_b(0);
         read_b(1);
-#pragma unroll
-        for (int kk = 0; kk < KCH; ++kk) {
-            if (kk + 2 < KCH) read_b(kk + 2);
+        static_for<0, KCH>([&](auto kk_c) {
+            constexpr int kk = decltype(kk_c)::value;
+            if constexpr (kk + 2 < KCH) read_b(kk + 2);
 #pragma unroll
             for (int io = 0; io < S::IO; ++io)
 #pragma unroll
                 for (int jt = 0; jt < S::JT; ++jt)
                     acc[io][jt] = Traits<T>::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
-        }
+            // the previous tile's results: job j rides in chunk j*KCH/6
+            static_for<0, 6>([&](auto job_c) {
+                constexpr int job = decltype(job_c)::value;
+                if constexpr (job * KCH / 6 == kk) flush_job(job);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
         park(lds + (cur ^ 1) * S::kBuf);       // the other buffer was last read before the previous barrier
-
-        // results: 16 tokens x 48 channels at a time through this wave's staging rows, then 16-byte
-        // stores that cover whole runs of a token's channels
-        const auto out = ep.tile(tile * S::TB);
 #pragma unroll
-        for (int jt = 0; jt < S::JT; ++jt) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+        for (int io = 0; io < S::IO; ++io)
 #pragma unroll
-            for (int io = 0; io < S::IO; ++io)
-                store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, frag_from_f32<T>(acc[io][jt]));
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row: 6
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int v = lane + 64 * i;
-                if (v < 16 * kVecRow) {
-                    const int row = v / kVecRow, cv = v % kVecRow;
-                    const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
-                    out.store(ch0, ch0 + S::kChanWave, jt * 16 + row, ch0 + cv * 8, val);
-                }
-            }
-        }
+            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
+        dest = ep.tile(tile * S::TB);
         __syncthreads();
         cur ^= 1;
     }
+#pragma unroll
+    for (int job = 0; job < 6; ++job) flush_job(job);
 }
 
 template <class T, int KCH, class Epilogue>
