@@ -18,9 +18,10 @@
 // A wave sweeps a 16-token-wide strip downwards: each input row is read once
 // from LDS and multiplied into the (up to) k rolling accumulators of the
 // output rows it touches.  The Toeplitz operands of a head's 48 channels are
-// built once per workgroup and stay in registers.  The workgroup is a two-stage pipeline: four waves
-// stage the next tile (global loads, transposition, raw branch) while four waves sweep the current
-// one (a 16-column strip x 8 rows each), so HBM latency and matrix-core work overlap inside a CU.
+// built once per wave and stay in registers.  The workgroup is a two-stage pipeline: four waves
+// stage the next tile (global loads, transposition, raw branch) while eight waves sweep the current
+// one (a 16-column strip x 4 rows each), so HBM latency and matrix-core work overlap inside a CU and
+// every SIMD hosts one staging and two sweeping waves.
 //
 // The halo tile is kept channel-planar in LDS ([channel][row][x], x contiguous),
 // which is what B_b wants; the global maps are token-major, so staging goes
@@ -43,9 +44,9 @@
 namespace msla {
 namespace {
 
-constexpr int MTH = kAggMfmaTileH;   // 16 tile rows: two halves of 8, one per wave pair
+constexpr int MTH = kAggMfmaTileH;   // 16 tile rows, split into groups of kSweepRows
 constexpr int MTW = kAggMfmaTileW;   // 32 tile columns: two 16-token strips
-constexpr int kSweepWaves = 8;       // 4 or 8: each sweeps a 16-column strip x 8 or 4 rows
+constexpr int kSweepWaves = 8;       // 4 or 8: each sweeps a 16-column strip x 8 or 4 rows (8: two per SIMD)
 constexpr int kThreads = (4 + kSweepWaves) * 64;     // 4 staging waves + the sweeping waves
 constexpr int kSweepRows = MTH / (kSweepWaves / 2);
 
@@ -382,23 +383,14 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                                                                     (unsigned)__shfl((int)l2[1], from)});
                 }
             } else {
-                // K, Q: the 16 channels x 16 tokens are written as they are -- 8 bytes per lane, in
-                // lane order, a [channel][token] matrix -- and picked up transposed by the LDS
-                // transpose read in stage 2
+                // K, Q: the lane's 4 tokens of one channel go into a [token][channel] fp32 matrix; stage 2
+                // picks up a token's 4 channels with one 16-byte read
                 char* tb = trans + (it & 1) * L::kTransBytes;
                 wave_lds_fence();
 #pragma unroll
                 for (int i = 0; i < 4; ++i) *(float*)(tb + (4 * sub + i) * L::kTokStride + chn * 4) = o[i];
                 wave_lds_fence();
             }
-        };
-        // ds_read_b64_tr_b16 on lane addresses base + 8*lane: lane (token x16, q) receives channels
-        // 4q..4q+3 of its token out of the [channel][token] matrix written above (within a group of
-        // 16 lanes, lane l gets element l%4 of the 8-byte chunks l/4, l/4 + 4, l/4 + 8, l/4 + 12).
-        auto read_transposed = [&](const char* p) {
-            typedef short s16x4 __attribute__((ext_vector_type(4)));
-            typedef __attribute__((address_space(3))) s16x4* LdsPtr;
-            return __builtin_bit_cast(Frag, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsPtr)(p + lane * 8)));
         };
         // Stage 2 is split: the transposed row is requested from LDS at the top of an iteration and
         // used after the iteration's depthwise MFMAs, which cover the LDS latency.
