@@ -11,6 +11,9 @@
 #define MSLA_PROJ_WC 2
 #endif
 
+#ifndef MSLA_WS_IO
+#define MSLA_WS_IO 3
+#endif
 #ifndef MSLA_WS_RESIDENT
 #define MSLA_WS_RESIDENT 2
 #endif
@@ -249,7 +252,7 @@ template <class T, int KCH>
 struct WsShape {
     static_assert(sizeof(T) == 2 && KCH % 2 == 0, "16-bit elements, whole 128-byte slabs");
     static constexpr int kWaves = 4, kThreads = 256, kResident = MSLA_WS_RESIDENT;
-    static constexpr int IO = 3;                         // 16-channel groups per wave
+    static constexpr int IO = MSLA_WS_IO;                // 16-channel groups per wave
     static constexpr int JT = 2;                         // 16-token groups per tile
     static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
     static constexpr int TB = JT * 16;                   // tokens per tile
