@@ -157,6 +157,23 @@ def main():
             stage_ms[s] += ev.elapsed_ms(5 * i + j, 5 * i + j + 1)
     ev.destroy()
     stage_ms = {s: v / args.steps for s, v in stage_ms.items()}
+    # ---- the practical ceiling: a plain device-to-device copy well beyond the memory-side cache
+    # (512 MiB read + 512 MiB written per copy), timed with events on the same stream
+    n_copy = 512 << 20
+    src = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    for _ in range(2):
+        dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * n_copy * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
     alg = stage_algorithmic_bytes(wl)
     dominant = max(STAGES, key=lambda s: stage_ms[s])
     achieved = alg[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
@@ -166,7 +183,8 @@ def main():
                 "algorithmic_bytes": alg[dominant], "avg_ms": round(stage_ms[dominant], 5),
                 "stage_ms": {s: round(v, 5) for s, v in stage_ms.items()},
                 "module_algorithmic_bytes": wl.algorithmic_bytes(),
-                "module_frac": round(wl.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                "module_frac": round(wl.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "measured_copy_gbs": round(copy_gbs, 1)}
 
     # ---- the fp64 CPU oracle as it stands, on the host cores (reported baseline + parity check)
     cpu = None
