@@ -22,9 +22,6 @@
 namespace msla {
 namespace {
 
-template <class T>
-using ApplyTile = GemmTile<T, MSLA_APPLY_WR, MSLA_APPLY_WC>;
-
 // q: channels 4q..4q+3 of this lane's token (raw, not yet rectified).
 // state: the 2048-byte operand block of (image, head-branch).  eps_s = eps * scale.
 template <class T>
@@ -96,20 +93,21 @@ __global__ __launch_bounds__(256) void apply_kernel(const T* __restrict__ q_ms, 
 }
 
 // ------------------------------------------------- att fused into projection
-// 128 tokens of one image x 256 output channels per workgroup, 8 waves.  Each
+// WC*64 tokens of one image x WR*64 output channels per workgroup, one wave per 64 x 64
+// (128 tokens x 256 channels, 8 waves, unless the map is small).  Each
 // iteration covers 128 contraction bytes = BK/16 head-branches; wave w makes
 // the attention rows of token group w for them and writes them to the token
 // tile in LDS while the weight tile arrives from the previous iteration's
 // prefetch.  For bf16 the attention rows go to LDS as a hi and a lo tile (two
 // MFMA passes), since 8 significant bits would cost half the error budget.
-template <class T>
-__global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(const T* __restrict__ q_ms,
+template <class T, int WR, int WC>
+__global__ __launch_bounds__(WR * WC * 64) void apply_project_kernel(const T* __restrict__ q_ms,
                                                             const char* __restrict__ kvfrag,
                                                             const float* __restrict__ kvscale,
                                                             const T* __restrict__ w_proj, T* __restrict__ out,
                                                             int N, int n_hb, int c_out, int blocks_per_image,
                                                             int n_rb, float eps) {
-    typedef ApplyTile<T> G;
+    typedef GemmTile<T, WR, WC> G;
     typedef typename Traits<T>::Frag Frag;
     constexpr int HB = G::BK / 16;   // head-branches per iteration
     constexpr int kWaves = G::kThreads / 64;
@@ -128,7 +126,7 @@ __global__ __launch_bounds__(ApplyTile<T>::kThreads) void apply_project_kernel(c
     const int n0 = (tb % blocks_per_image) * G::BC;
     const int oc0 = rb * G::BR;
     const int wave = threadIdx.x >> 6;
-    const int wr = wave % MSLA_APPLY_WR, wc = wave / MSLA_APPLY_WR;
+    const int wr = wave % WR, wc = wave / WR;
     const int x16 = lane_id() & 15, q = lane_id() >> 4;
     const int K = n_hb * 16;
 
@@ -633,6 +631,26 @@ hipError_t run_apply(const void* q_ms, const void* kvfrag, const float* kvscale,
     return hipGetLastError();
 }
 
+template <class T, int WR, int WC>
+hipError_t run_apply_project_tiled(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
+                                   void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
+                                   hipStream_t stream) {
+    typedef GemmTile<T, WR, WC> G;
+    const int bpi = (N + G::BC - 1) / G::BC;
+    const int n_rb = (c_out + G::BR - 1) / G::BR;
+    const long nblocks = (n_tokens / N) * bpi * n_rb;
+    if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    constexpr int kLds = G::kLdsR + G::kLdsC * (Traits<T>::kHiLo ? 2 : 1);
+    if (kLds > 48 * 1024) {   // above the default dynamic-LDS limit (the CU has 160 KB)
+        const hipError_t e = allow_dynamic_lds<apply_project_kernel<T, WR, WC>>(kLds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((apply_project_kernel<T, WR, WC>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream,
+                       (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb, c_out,
+                       bpi, n_rb, eps);
+    return hipGetLastError();
+}
+
 template <class T>
 hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
                              void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
@@ -653,20 +671,14 @@ hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* 
         }
     }
 #endif
-    typedef ApplyTile<T> G;
-    const int bpi = (N + G::BC - 1) / G::BC;
-    const int n_rb = (c_out + G::BR - 1) / G::BR;
-    const long nblocks = (n_tokens / N) * bpi * n_rb;
-    if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    constexpr int kLds = G::kLdsR + G::kLdsC * (Traits<T>::kHiLo ? 2 : 1);
-    if (kLds > 48 * 1024) {   // above the default dynamic-LDS limit (the CU has 160 KB)
-        const hipError_t e = allow_dynamic_lds<apply_project_kernel<T>>(kLds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((apply_project_kernel<T>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream,
-                       (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb, c_out,
-                       bpi, n_rb, eps);
-    return hipGetLastError();
+    // Tiled form: 64 x 64 per wave, 256 channels x 128 tokens per workgroup; a map too small to give
+    // every CU such a tile takes 64-token tiles (measured on the 2048- and 1024-token workloads: 33
+    // against 45 us and 17 against 25 us; still smaller workgroups were slower again)
+    const long blocks = (n_tokens / N) * ((N + 64 * MSLA_APPLY_WC - 1) / (64 * MSLA_APPLY_WC)) *
+                        ((c_out + 64 * MSLA_APPLY_WR - 1) / (64 * MSLA_APPLY_WR));
+    if (MSLA_APPLY_WC == 2 && blocks < compute_units())
+        return run_apply_project_tiled<T, MSLA_APPLY_WR, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+    return run_apply_project_tiled<T, MSLA_APPLY_WR, MSLA_APPLY_WC>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
 }
 
 }  // namespace
