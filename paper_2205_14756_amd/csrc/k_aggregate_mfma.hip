@@ -574,6 +574,9 @@ hipError_t run(const AggregateArgs& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream) {
+#ifdef MSLA_AGG_NO_MFMA
+    return hipErrorNotSupported;      // build knob: every case takes the general kernel (as oversized images do)
+#endif
     switch (dt) {
         case 1: return run<_Float16>(a, stream);
         case 2: return run<__bf16>(a, stream);

@@ -5,6 +5,7 @@
 #include "../../include/msla.h"
 
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "msla_kernels.h"
 
@@ -120,10 +121,22 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
         a.branch = i + 1;
         a.do_raw = (i == 0);
         a.copy_raw_q = (i == 0) ? copy_raw_q : 0;
+        // (MSLA_AGG_GENERAL=1 in the environment sends every case to the general kernel: that is how
+        // the tests reach the path below without a 2 GiB image)
+        const char* force = getenv("MSLA_AGG_GENERAL");
+        const bool general = dt == MSLA_F32 || (force && force[0] == '1');
         hipError_t e_launch = (dt == MSLA_F32) ? msla::launch_aggregate((int)dt, a, stream)
+                              : general        ? hipErrorNotSupported
                                                : msla::launch_aggregate_mfma((int)dt, a, stream);
-        // an image whose maps exceed the matrix-core kernel's 32-bit offsets takes the general kernel
-        if (e_launch == hipErrorNotSupported) e_launch = msla::launch_aggregate((int)dt, a, stream);
+        // an image whose maps exceed the matrix-core kernel's 32-bit offsets takes the general kernel,
+        // whose tiles are half as high: the same number of chunks, twice the tiles in each
+        if (e_launch == hipErrorNotSupported) {
+            msla::AggregateArgs g = a;
+            const long tiles = (long)((s.H + msla::kAggTileH - 1) / msla::kAggTileH) *
+                               ((s.W + msla::kAggTileW - 1) / msla::kAggTileW);
+            g.tiles_per_chunk = (int)((tiles + a.nchunks - 1) / a.nchunks);
+            e_launch = msla::launch_aggregate((int)dt, g, stream);
+        }
         if (e_launch != hipSuccess) return MSLA_ERR_LAUNCH;
     }
     if (event_before_finalize &&

@@ -225,6 +225,20 @@ def test_forward_several_tiles_per_workgroup(dtype, B, C, H, W, heads, scales):
     check_module(t, dtype, heads, d, scales)
 
 
+@pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
+    ("f16", 2, 64, 37, 70, 4, (3, 5)),
+    ("bf16", 1, 128, 64, 64, 8, (5,)),
+])
+def test_forward_general_aggregation_kernel_for_16_bit_types(dtype, B, C, H, W, heads, scales, monkeypatch):
+    """An image whose maps span 2 GiB or more leaves the matrix-core aggregation kernel for the
+    general one (half-height tiles, same chunks); MSLA_AGG_GENERAL=1 takes that path at any size."""
+    d = 16
+    monkeypatch.setenv("MSLA_AGG_GENERAL", "1")
+    print(f"forward, general aggregation kernel: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
+    t = wk.random_module(4242 + C + H, dtype, B, C, H, W, heads, d, scales)
+    check_module(t, dtype, heads, d, scales)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_forward_benchmark_configs_full_size(cfg):
     """The five workload shapes at full size, in the launch configuration the bench times."""
