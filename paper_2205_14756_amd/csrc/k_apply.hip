@@ -14,6 +14,9 @@
 #include "gemm_tile.h"
 #include "msla_kernels.h"
 
+#ifndef MSLA_APPLY_W_AHEAD
+#define MSLA_APPLY_W_AHEAD 3
+#endif
 #ifndef MSLA_APPLY_WR
 #define MSLA_APPLY_WR 4
 #define MSLA_APPLY_WC 2
@@ -311,13 +314,16 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
 
     // ---- weights -> registers, copied in row order through LDS (fragment reads straight from
-    // memory would touch one cache line per lane).  All slabs are requested at once: the registers
-    // they wait in are the ones the fragments move into, and the memory latency is paid once.
+    // memory would touch one cache line per lane).  The registers the slabs wait in are the ones the
+    // fragments move into.  The CU's address path needs longer for the 32 loads per thread than the
+    // data takes to arrive, so the requests run kAheadW slabs ahead of the staging instead of all
+    // being issued first: the staging of a slab then overlaps with the requests of the later ones.
     Vec wf[IO][KCH];
     const int g16 = (x16 >> 1) & 7;
     {
         const BufRsrc wres = make_rsrc(w_proj, (long)c_out * row_bytes);
         constexpr int kWV = S::kChanBlock * 8 / S::kThreads;      // vectors per thread and slab
+        constexpr int kAheadW = S::NS < MSLA_APPLY_W_AHEAD ? S::NS : MSLA_APPLY_W_AHEAD;
         unsigned base[kWV];
         int wl[kWV];
 #pragma unroll
@@ -328,17 +334,20 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             wl[i] = r * S::kRow + lds_swizzle(r, threadIdx.x & 7) * 16;
         }
         u32x4 wr[S::NS][kWV];
-#pragma unroll
-        for (int sl = 0; sl < S::NS; ++sl)
+        auto request = [&](int sl) {
 #pragma unroll
             for (int i = 0; i < kWV; ++i)
                 wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
                                                  ? base[i] + sl * 128 : kOobOffset, 0);
+        };
+#pragma unroll
+        for (int sl = 0; sl < kAheadW; ++sl) request(sl);
 #pragma unroll
         for (int sl = 0; sl < S::NS; ++sl) {
             if (sl) __syncthreads();
 #pragma unroll
             for (int i = 0; i < kWV; ++i) *(u32x4*)(lds + wl[i]) = wr[sl][i];
+            if (sl + kAheadW < S::NS) request(sl + kAheadW);
             __syncthreads();
 #pragma unroll
             for (int io = 0; io < IO; ++io)
