@@ -317,18 +317,24 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
             const int row = cg * S::kChanBlock + ((threadIdx.x + i * S::kThreads) >> 3);
             base[i] = row < c_out ? (unsigned)ep.row_of(row) * row_bytes + (threadIdx.x & 7) * 16 : kOobOffset;
         }
-#pragma unroll
-        for (int sl = 0; sl < S::NS; ++sl)
+        // (the requests run two slabs ahead of the staging: the address path is busy with them for
+        // longer than the data takes to arrive, so staging a slab overlaps with requesting later ones)
+        auto request = [&](int sl) {
 #pragma unroll
             for (int i = 0; i < kWV; ++i)
                 wr[sl][i] = buf_load16(wres, (base[i] != kOobOffset && sl * 128 + (threadIdx.x & 7) * 16 < row_bytes)
                                                  ? base[i] + sl * 128 : kOobOffset, 0);
+        };
+        constexpr int kAheadW = S::NS < 2 ? S::NS : 2;
+#pragma unroll
+        for (int sl = 0; sl < kAheadW; ++sl) request(sl);
 #pragma unroll
         for (int sl = 0; sl < S::NS; ++sl) {
             if (sl) __syncthreads();
 #pragma unroll
             for (int i = 0; i < kWV; ++i)
                 *(u32x4*)(lds + ((threadIdx.x + i * S::kThreads) >> 3) * S::kRow + (threadIdx.x & 7) * 16) = wr[sl][i];
+            if (sl + kAheadW < S::NS) request(sl + kAheadW);
             __syncthreads();
 #pragma unroll
             for (int io = 0; io < S::IO; ++io)
