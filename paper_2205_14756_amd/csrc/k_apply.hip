@@ -481,7 +481,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             const int row = lane / kVecRow, cv = lane % kVecRow;
             const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
             const int oc = ch0 + cv * 8;
-            buf_store16(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
+            buf_store16_stream(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
