@@ -169,17 +169,22 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     const unsigned lane_k_off = x16 * k_tb + q * 8 * (unsigned)sizeof(T);
 
     // ---------------- staging: token-major global -> channel-planar LDS, raw branch on the way.
-    // Halo rows are dealt to the waves round-robin and handled two at a time ("batch": 12 loads).
-    // A row has 3 groups of 16 columns; lane (token x16, q) loads its token's 4 Q channels and 8 of
-    // its 32 K|V channels, and after the selection MFMA lane (channel x16, q) holds tokens
-    // lx0 + 4q .. + 3 of that channel.  The loads of the next batch are issued before the current one
-    // is consumed, so they are in flight during its MFMAs.
+    // Halo rows are dealt to the waves round-robin (row w4 + 4j, j = 0..4) and handled two at a time
+    // ("batch").  A row's first 32 columns are two groups of 16: lane (token x16, q) loads its
+    // token's 4 Q channels and 8 of its 32 K|V channels, and after the selection MFMA lane
+    // (channel x16, q) holds tokens lx0 + 4q .. + 3 of that channel.  The last 2P columns of the wave's
+    // rows j = 0..3 share one more such load (token slot x16 = 4*(j) + column - 32), row 4 has a
+    // mostly empty one of its own: a wave-level load costs the same however few of its lanes are live.
+    // The loads of the next batch are issued before the current one is consumed, so they are in
+    // flight during its MFMAs.
     struct Batch {
-        Frag qf[2][3];
-        u32x4 kvr[2][3];
+        Frag qf[2][2], qtail;
+        u32x4 kvr[2][2], kvtail;
     };
     constexpr int kBatches = ((L::LH + 3) / 4 + 1) / 2;
-    static_assert(kBatches == 3, "staging schedule below assumes 3 batches per tile");
+    static_assert(kBatches == 3 && L::LW - 32 <= 4 && L::LH <= 20, "staging schedule below: 3 batches, 5 rows per wave, a 4-column tail");
+    // tail slots of batch `it`: rows j = jbase + (x16 >> 2), column 32 + (x16 & 3)
+    auto tail_jbase = [](int it) { return it == 2 ? 0 : 4; };
 
     auto issue = [&](int tile_id, int it, Batch& bt, bool live) {   // staging waves; !live: every lane masked
         const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
@@ -192,12 +197,21 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             const unsigned tok_first = (unsigned)(gy * a.W + (tx0 - P));
             const unsigned qrow = tok_first * q_tb + lane_q_off, krow = tok_first * k_tb + lane_k_off;
 #pragma unroll
-            for (int cg = 0; cg < 3; ++cg) {
-                const int lx = cg * 16 + x16, gx = tx0 - P + lx;
-                const bool ok = row_ok && gx >= 0 && gx < a.W && lx < L::LW;
+            for (int cg = 0; cg < 2; ++cg) {
+                const int gx = tx0 - P + cg * 16 + x16;
+                const bool ok = row_ok && gx >= 0 && gx < a.W;
                 bt.qf[rr][cg] = __builtin_bit_cast(Frag, buf_load8(rq, ok ? qrow + cg * 16 * q_tb : kOobOffset));
                 bt.kvr[rr][cg] = buf_load16(rk, ok ? krow + cg * 16 * k_tb : kOobOffset, 0);
             }
+        }
+        if (it != 0) {
+            const int j = tail_jbase(it) + (x16 >> 2), lx = 32 + (x16 & 3);
+            const int ly = w4 + 4 * j;
+            const int gy = ty0 - P + ly, gx = tx0 - P + lx;
+            const bool ok = live && j <= 4 && ly < L::LH && lx < L::LW && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W;
+            const unsigned tok = (unsigned)(gy * a.W + gx);
+            bt.qtail = __builtin_bit_cast(Frag, buf_load8(rq, ok ? tok * q_tb + q * 4 * (unsigned)sizeof(T) : kOobOffset));
+            bt.kvtail = buf_load16(rk, ok ? tok * k_tb + q * 8 * (unsigned)sizeof(T) : kOobOffset, 0);
         }
     };
 
@@ -211,11 +225,11 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             const bool row_interior = ly >= P && ly < P + MTH;
             const long tok_first = img_tok0 + (long)gy * a.W + (tx0 - P);
             char* dst_row = planar + x16 * L::kChanBytes + ly * L::kRowBytes + q * 8;
-            // All nine selection MFMAs of the row are issued before any result is touched, so their
+            // All six selection MFMAs of the row are issued before any result is touched, so their
             // latencies overlap (a conversion right behind its MFMA stalls the wave for the whole pass).
-            f32x4 sq[3], sk[3], sv[3];
+            f32x4 sq[2], sk[2], sv[2];
 #pragma unroll
-            for (int cg = 0; cg < 3; ++cg) {
+            for (int cg = 0; cg < 2; ++cg) {
                 const Vec kvv = __builtin_bit_cast(Vec, bt.kvr[rr][cg]);
                 sq[cg] = Tr::mma16(z, bt.qf[rr][cg], ident);
                 sk[cg] = Tr::mma_vec(z, kvv, selk);
@@ -223,34 +237,66 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int cg = 0; cg < 3; ++cg) {
+            for (int cg = 0; cg < 2; ++cg) {
                 const int lx0 = cg * 16;
-                const bool writes = cg < 2 || q == 0;       // the third group only has columns 32..35
                 const Frag dq = frag_from_f32<T>(sq[cg]);
                 const Frag dk = frag_from_f32<T>(sk[cg]);
                 const Frag dv = frag_from_f32<T>(sv[cg]);
-                if (writes) {
-                    store_frag<T>(dst_row + lx0 * 2, dq);
-                    store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
-                    store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
-                }
+                store_frag<T>(dst_row + lx0 * 2, dq);
+                store_frag<T>(dst_row + 16 * L::kChanBytes + lx0 * 2, dk);
+                store_frag<T>(dst_row + 32 * L::kChanBytes + lx0 * 2, dv);
                 if constexpr (kCopyRawQ) {
-                    if (row_interior && lx0 + x16 >= P && lx0 + x16 < P + MTW && gy < a.H && tx0 - P + lx0 + x16 < a.W)
+                    if (row_interior && lx0 + x16 >= P && gy < a.H && tx0 - P + lx0 + x16 < a.W)
                         store_frag<T>(q_ms + (tok_first + lx0 + x16) * q_ms_ts + h * 16 + q * 4, bt.qf[rr][cg]);
                 }
                 if (a.do_raw && row_interior) {
                     // raw branch: tokens of this tile's interior only (each token belongs to one tile)
                     Frag rk = frag_relu_bits<T>(dk);
-                    if (cg != 1) {      // the outer column groups contain halo columns
+                    if (cg == 0) {      // the first columns are halo
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int lx = lx0 + 4 * q + r;
-                            if (lx < P || lx >= P + MTW) rk[r] = Tr::from_f32(0.f);
-                        }
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * q + r < P) rk[r] = Tr::from_f32(0.f);
                     }
                     ks_raw4 = Tr::mma16(ks_raw4, rk, ones);
                     kv_raw = Tr::mma16(kv_raw, rk, dv);
                 }
+            }
+        }
+        if (it != 0) {
+            // the tail columns: lane (channel x16, q) ends up with columns 32..35 of row j = jbase + q
+            const int j = tail_jbase(it) + q;
+            const int ly = w4 + 4 * j;
+            const bool row_ok = j <= 4 && ly < L::LH;
+            const bool row_interior = row_ok && ly >= P && ly < P + MTH;
+            const Vec kvv = __builtin_bit_cast(Vec, bt.kvtail);
+            const f32x4 tq = Tr::mma16(z, bt.qtail, ident);
+            const f32x4 tk = Tr::mma_vec(z, kvv, selk);
+            const f32x4 tv = Tr::mma_vec(z, kvv, selv);
+            __builtin_amdgcn_sched_barrier(0);
+            const Frag dq = frag_from_f32<T>(tq);
+            const Frag dk = frag_from_f32<T>(tk);
+            const Frag dv = frag_from_f32<T>(tv);
+            if (row_ok) {
+                char* dst = planar + x16 * L::kChanBytes + ly * L::kRowBytes + 32 * 2;
+                store_frag<T>(dst, dq);
+                store_frag<T>(dst + 16 * L::kChanBytes, dk);
+                store_frag<T>(dst + 32 * L::kChanBytes, dv);
+            }
+            if constexpr (kCopyRawQ) {
+                // here the lane is still (token slot x16, q): row jbase + (x16 >> 2), column 32 + (x16 & 3)
+                const int js = tail_jbase(it) + (x16 >> 2), lxs = 32 + (x16 & 3);
+                const int lys = w4 + 4 * js;
+                const int gys = ty0 - P + lys, gxs = tx0 - P + lxs;
+                if (js <= 4 && lys >= P && lys < P + MTH && lxs < P + MTW && gys < a.H && gxs < a.W)
+                    store_frag<T>(q_ms + (img_tok0 + (long)gys * a.W + gxs) * q_ms_ts + h * 16 + q * 4, bt.qtail);
+            }
+            if (a.do_raw) {
+                Frag rk = frag_relu_bits<T>(dk);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (!row_interior || 32 + r >= P + MTW) rk[r] = Tr::from_f32(0.f);
+                ks_raw4 = Tr::mma16(ks_raw4, rk, ones);
+                kv_raw = Tr::mma16(kv_raw, rk, dv);
             }
         }
     };
