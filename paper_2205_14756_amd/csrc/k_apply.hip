@@ -307,7 +307,14 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     auto fetch_q1 = [&](int i) {
         qv[i] = buf_load16(qres, q_slab * 128 + q_chunk * 16 + i * 256 < row_bytes ? q_glb + i * 256 : kOobOffset, 0);
     };
-    auto park_q1 = [&](char* qb, int i) { *(u32x4*)(qb + q_lds + 2 * i * S::kSlab) = qv[i]; };
+    // Eq. (3) only ever sees relu(Q): the rectifier is applied here, once per element, as integer
+    // maxima on the bit patterns (negative values and -0 have the sign bit set)
+    auto park_q1 = [&](char* qb, int i) {
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        const i16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        const i16x8 r = __builtin_elementwise_max(__builtin_bit_cast(i16x8, qv[i]), zero);
+        *(u32x4*)(qb + q_lds + 2 * i * S::kSlab) = __builtin_bit_cast(u32x4, r);
+    };
 
     aim_q(first, true);      // requested ahead of the weights, so the first tile does not queue behind them
 #pragma unroll
@@ -389,7 +396,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     auto att_a = [&](const char* qb, int u) { att_q[u & 1] = load_frag<T>((const T*)(qb + unit_off(u))); };
     auto att_b = [&](int u) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        const Frag qf = frag_relu<T>(att_q[u & 1]);
+        const Frag qf = att_q[u & 1];         // rectified when the tile was parked
         Vec b;
 #pragma unroll
         for (int r = 0; r < 4; ++r) { b[r] = qf[r]; b[4 + r] = qf[r]; }   // pairs with {hi, lo} of the state
