@@ -48,6 +48,17 @@ struct PlainDest {
         const long rb = (long)c_out * (long)sizeof(T);
         return Tile{make_rsrc(y + tok0 * c_out, (n_tokens - tok0) * rb), (unsigned)rb, c_out};
     }
+    // A lane's part of a store that does not change from tile to tile: its byte offset inside a
+    // group of 16 token rows (beyond every resource where the lane has nothing to write).
+    struct Lane {
+        unsigned off;
+    };
+    __device__ __forceinline__ Lane lane(int row, int oc, bool live) const {
+        return Lane{live && oc < c_out ? (unsigned)row * (unsigned)(c_out * sizeof(T)) + oc * (unsigned)sizeof(T) : kOobOffset};
+    }
+    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int, int, int row0, u32x4 v) {
+        buf_store16_at(t.y, l.off, (unsigned)row0 * t.row_bytes, v);
+    }
 };
 
 // Q/K/V projection with split destinations.  The kernel walks the output channels in DESTINATION
@@ -82,6 +93,20 @@ struct QkvSplitDest {
         const long qb = q_ms_stride * (long)sizeof(T), kb = kv_stride * (long)sizeof(T);
         return Tile{make_rsrc(q_ms + tok0 * q_ms_stride, (n_tokens - tok0) * qb),
                     make_rsrc(kv_raw + tok0 * kv_stride, (n_tokens - tok0) * kb), (unsigned)qb, (unsigned)kb, Ct};
+    }
+    struct Lane {
+        unsigned q, kv;
+    };
+    __device__ __forceinline__ Lane lane(int row, int vc, bool live) const {
+        constexpr unsigned sz = (unsigned)sizeof(T);
+        const unsigned qb = (unsigned)(q_ms_stride * sizeof(T)), kb = (unsigned)(kv_stride * sizeof(T));
+        return Lane{live && vc < Ct ? (unsigned)row * qb + vc * sz : kOobOffset,
+                    live && vc >= Ct && vc < 3 * Ct ? (unsigned)row * kb + (vc - Ct) * sz : kOobOffset};
+    }
+    // piece0 .. piece_end: the wave's channel range, which tells (wave-uniformly) which maps it touches
+    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int piece0, int piece_end, int row0, u32x4 v) {
+        if (piece0 < t.Ct) buf_store16_at(t.q, l.q, (unsigned)row0 * t.q_row_bytes, v);
+        if (piece_end > t.Ct) buf_store16_at(t.kv, l.kv, (unsigned)row0 * t.kv_row_bytes, v);
     }
 };
 
@@ -381,13 +406,16 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
             if (v < 16 * kVecRow) held[i] = *(const u32x4*)(stage + (v / kVecRow) * S::kStageRow + (v % kVecRow) * 16);
         }
     };
+    typename Epilogue::Lane where[2];      // this lane's two words of a 16-token piece: fixed for the kernel
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int v = lane + 64 * i;
+        where[i] = ep.lane(v / kVecRow, ch0 + (v % kVecRow) * 8, v < 16 * kVecRow);
+    }
     auto flush_s = [&](int jt) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int v = lane + 64 * i;
-            if (v < 16 * kVecRow)
-                dest.store(ch0, ch0 + S::kChanWave, jt * 16 + v / kVecRow, ch0 + (v % kVecRow) * 8, held[i]);
-        }
+        for (int i = 0; i < 2; ++i)
+            if (64 * i < 16 * kVecRow) Epilogue::store(dest, where[i], ch0, ch0 + S::kChanWave, jt * 16, held[i]);
     };
     auto flush_job = [&](int job) {       // w0 r0 s0 w1 r1 s1
         if (job % 3 == 0) flush_w(job / 3);

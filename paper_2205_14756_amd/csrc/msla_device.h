@@ -218,6 +218,10 @@ __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, unsigned voffset, int sof
 __device__ __forceinline__ void buf_store16(BufRsrc r, unsigned voffset, u32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, 0, 0);
 }
+// ... with a wave-uniform byte offset on top (never negative; the range check sees only voffset)
+__device__ __forceinline__ void buf_store16_at(BufRsrc r, unsigned voffset, unsigned soffset, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, (int)soffset, 0);
+}
 // The same store with the non-temporal hint: for output that no later kernel of the module reads
 // (it then does not displace the maps the next call's kernels re-read from the caches).
 __device__ __forceinline__ void buf_store16_stream(BufRsrc r, unsigned voffset, u32x4 v) {
