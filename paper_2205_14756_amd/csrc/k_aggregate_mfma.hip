@@ -151,6 +151,16 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
 
     const int tiles_x = (a.W + MTW - 1) / MTW, tiles_y = (a.H + MTH - 1) / MTH;
     const int n_tiles = tiles_x * tiles_y;
+    // a tile's first row and column, stepped along the row-major tile order without divisions
+    struct TileAt {
+        int ty0, tx0;
+    };
+    auto tile_at = [&](int tile_id) { return TileAt{(tile_id / tiles_x) * MTH, (tile_id % tiles_x) * MTW}; };
+    auto tile_after = [&](TileAt t) {
+        t.tx0 += MTW;
+        if (t.tx0 >= tiles_x * MTW) { t.tx0 = 0; t.ty0 += MTH; }
+        return t;
+    };
     const int tile_begin = chunk * a.tiles_per_chunk;
     const int tile_end = min(n_tiles, tile_begin + a.tiles_per_chunk);
 
@@ -186,8 +196,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // tail slots of batch `it`: rows j = jbase + (x16 >> 2), column 32 + (x16 & 3)
     auto tail_jbase = [](int it) { return it == 2 ? 0 : 4; };
 
-    auto issue = [&](int tile_id, int it, Batch& bt, bool live) {   // staging waves; !live: every lane masked
-        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+    auto issue = [&](TileAt at, int it, Batch& bt, bool live) {   // staging waves; !live: every lane masked
+        const int ty0 = at.ty0, tx0 = at.tx0;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             const int ly = w4 + 4 * (it + rr);
@@ -215,8 +225,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         }
     };
 
-    auto consume = [&](int tile_id, int it, const Batch& bt, char* planar) {
-        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+    auto consume = [&](TileAt at, int it, const Batch& bt, char* planar) {
+        const int ty0 = at.ty0, tx0 = at.tx0;
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             const int ly = w4 + 4 * (it + rr);
@@ -319,22 +329,24 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // loads as well).
     if (role == 0) {
         Batch ring0, ring1, ring2;
-        issue(tile_begin, 0, ring0, n_my_tiles > 0);
+        TileAt here = tile_at(tile_begin);
+        issue(here, 0, ring0, n_my_tiles > 0);
         __builtin_amdgcn_sched_barrier(0);
-        issue(tile_begin, 2, ring1, n_my_tiles > 0);
+        issue(here, 2, ring1, n_my_tiles > 0);
         __builtin_amdgcn_sched_barrier(0);
-        issue(tile_begin, 4, ring2, n_my_tiles > 0);
+        issue(here, 4, ring2, n_my_tiles > 0);
         __builtin_amdgcn_sched_barrier(0);
         for (int i = 0; i < n_my_tiles; ++i) {
-            const int tile_id = tile_begin + i;
+            const TileAt next = tile_after(here);
             const bool more = i + 1 < n_my_tiles;
             char* planar = lds + (i & 1) * L::kPlanarBytes;
-            consume(tile_id, 0, ring0, planar);
-            issue(tile_id + 1, 0, ring0, more);
-            consume(tile_id, 2, ring1, planar);
-            issue(tile_id + 1, 2, ring1, more);
-            consume(tile_id, 4, ring2, planar);
-            issue(tile_id + 1, 4, ring2, more);
+            consume(here, 0, ring0, planar);
+            issue(next, 0, ring0, more);
+            consume(here, 2, ring1, planar);
+            issue(next, 2, ring1, more);
+            consume(here, 4, ring2, planar);
+            issue(next, 4, ring2, more);
+            here = next;
             __syncthreads();
         }
         __syncthreads();
@@ -377,11 +389,12 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     // grouped 1x1 weights of Q and K as 16x16 operands: lane (o, q) holds w[o][4q..4q+3]
     const Frag gpw_q = load_frag<T>(wgp + (0 * 16 + x16) * 16 + q * 4);
     const Frag gpw_k = load_frag<T>(wgp + (1 * 16 + x16) * 16 + q * 4);
+    TileAt here = tile_at(tile_begin);
     for (int step = -1; step < n_my_tiles; ++step) {
         if (step >= 0) {
-        const int tile_id = tile_begin + step;
         const char* planar = lds + (step & 1) * L::kPlanarBytes;
-        const int ty0 = (tile_id / tiles_x) * MTH, tx0 = (tile_id % tiles_x) * MTW;
+        const int ty0 = here.ty0, tx0 = here.tx0;
+        here = tile_after(here);
         // ---------------- depthwise sweep: this wave's strip (16 columns) x part (kSweepRows rows)
         constexpr int R = kSweepRows;
         const int col0 = 16 * strip + 4 * sub;            // interior column of this lane's x-block
