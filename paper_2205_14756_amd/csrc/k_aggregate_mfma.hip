@@ -411,6 +411,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
         f32x4 acc[KS];
         Frag s1v[2][2];                   // V (hi, lo) after the lane permutation
         f32x4 s2v[2];                     // MFMA results awaiting stage 3
+        u32x2 q_held = {0u, 0u};          // an even Q row awaiting its partner
         auto pass_t = [](int pass) { return pass == 0 ? 1 : pass == 1 ? 2 : 0; };     // K, V, Q
         // A finished row sits as lane (channel chn, x-block sub) = 4 tokens of one channel.  It is
         // rounded to the operand type first (hi and lo halves for bf16), so everything that moves is
@@ -490,12 +491,23 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 if constexpr (Tr::kHiLo) frag_split<T>(kf, aggK[y], aggK_lo[y]);
                 else aggK[y] = frag_from_f32<T>(kf);
             } else if (t == 0) {
-                // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3
-                const int gy = gy0 + y;
-                const int gx = tx0 + 16 * strip + x16;
-                const unsigned off = (unsigned)(gy * a.W + gx) * q_ms_tb + q * 4 * (unsigned)sizeof(T);
-                buf_store8(rout, gy < a.H && gx < a.W ? off : kOobOffset,
-                           __builtin_bit_cast(u32x2, frag_from_f32<T>(s2v[it & 1])));
+                // lane (token x16 = 4*xblock + i, q): channels 4q..4q+3 of image row gy0 + y, 8 bytes.
+                // Two rows share one store (a store instruction costs the same whatever its width): an
+                // even row waits for the next one, then the odd 16-lane groups of the one are swapped
+                // with the even groups of the other, which leaves lane (x16, q) with channels
+                // 8*(q/2) .. +7 of its token in row y - 1 + q % 2.
+                static_assert(R % 2 == 0, "Q rows are stored in pairs");
+                const u32x2 v = __builtin_bit_cast(u32x2, frag_from_f32<T>(s2v[it & 1]));
+                if (y % 2 == 0) {
+                    q_held = v;
+                } else {
+                    const u32x2 s0 = __builtin_amdgcn_permlane16_swap(q_held[0], v[0], false, false);
+                    const u32x2 s1 = __builtin_amdgcn_permlane16_swap(q_held[1], v[1], false, false);
+                    const int gy = gy0 + y - 1 + (q & 1);
+                    const int gx = tx0 + 16 * strip + x16;
+                    const unsigned off = (unsigned)(gy * a.W + gx) * q_ms_tb + (q >> 1) * 8 * (unsigned)sizeof(T);
+                    buf_store16(rout, gy < a.H && gx < a.W ? off : kOobOffset, u32x4{s0[0], s1[0], s0[1], s1[1]});
+                }
             }
         };
         // input row i of the flat sequence: 8 columns (two k-steps) of this lane's channel and x-block
