@@ -241,11 +241,9 @@ struct WsApply {
     static constexpr int kSlab = TB * kRow;
     static constexpr int kBuf = NS * kSlab;              // one attention tile or Q tile
     static constexpr int kQV = NS / 2;                   // 16-byte vectors per thread of a Q tile
-    static constexpr int kStageRow = kChanWave * 2 + 16;
-    static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kWeightStage = kChanBlock * kRow;
     static constexpr int kTiles = 4 * kBuf;              // two attention tiles (or hi, lo) and two Q tiles
-    static constexpr int kLds = kTiles + kWaves * kStageWave;
+    static constexpr int kLds = kTiles;
     static_assert(kWeightStage <= kTiles, "the weights are staged through the tile area");
     static_assert(NS % 2 == 0 && TB * 16 == kThreads, "the Q tile copy takes two slabs per pass");
     static_assert(KCH == 2 * kUnits, "one attention unit per two chunks of matrix instructions");
@@ -434,7 +432,6 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     constexpr int kAhead = IO * KCH >= 32 ? 1 : 2;
     constexpr int kRing = kAhead + 1;
     f32x4 acc[IO][S::JT];
-    char* stage = lds + S::kTiles + wave * S::kStageWave;
     const int frag_off = x16 * S::kRow + (q ^ g16) * 16;       // chunk (kk&1)*4 + q: the second half is ^ 64
     Vec bf[kRing][S::JT];
     auto read_b = [&](const char* tile, int kk) {
@@ -456,9 +453,14 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
     };
 
-    // ---- results: finish() rounds a tile's accumulators into registers; the two pieces (16 tokens
-    // each) then go through this wave's staging rows -- flush_a parks one, flush_b writes it out as
-    // 16-byte words, whole runs of a token's channels.
+    // ---- results: finish() rounds a tile's accumulators into registers, a lane (token x16, q)
+    // holding channels 4q..4q+3 of each 16-channel block: 8 bytes.  flush(p) writes piece p out with
+    // one 16-byte store per lane: the odd 16-lane groups of one block are swapped with the even
+    // groups of another, which leaves a lane with 8 consecutive channels -- of the two channel blocks
+    // of 16 tokens (IO == 2: channels 16*(q%2) + 8*(q/2) .. +7 of token x16), or of one channel block
+    // of both token groups (IO == 1: channels 8*(q/2) .. +7 of token 16*(q%2) + x16).
+    static_assert(IO == 1 || IO == 2, "two 8-byte halves per store");
+    constexpr int kPieces = IO == 2 ? S::JT : S::JT / 2;
     Frag pend[IO][S::JT];
     BufRsrc ores;
     const unsigned out_row = (unsigned)c_out * 2u;
@@ -472,34 +474,26 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
         ores = make_rsrc(out + ((long)o.b * N + o.n0) * c_out, (long)rows * out_row);
     };
-    auto flush_a = [&](int jt) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int io = 0; io < IO; ++io)
-            store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    auto flush_b = [&](int jt) {
-        constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row
-        if (lane < 16 * kVecRow) {
-            const int row = lane / kVecRow, cv = lane % kVecRow;
-            const u32x4 val = *(const u32x4*)(stage + row * S::kStageRow + cv * 16);
-            const int oc = ch0 + cv * 8;
-            buf_store16_stream(ores, oc < c_out ? (unsigned)(jt * 16 + row) * out_row + oc * 2u : kOobOffset, val);
+    auto flush = [&](int p) {
+        u32x2 even, odd;
+        if constexpr (IO == 2) {
+            even = __builtin_bit_cast(u32x2, pend[0][p]);
+            odd = __builtin_bit_cast(u32x2, pend[IO - 1][p]);
+        } else {
+            even = __builtin_bit_cast(u32x2, pend[0][2 * p]);
+            odd = __builtin_bit_cast(u32x2, pend[0][2 * p + 1]);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        const u32x2 s0 = __builtin_amdgcn_permlane16_swap(even[0], odd[0], false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane16_swap(even[1], odd[1], false, false);
+        const int row = IO == 2 ? p * 16 + x16 : (2 * p + (q & 1)) * 16 + x16;
+        const int oc = ch0 + (IO == 2 ? (q & 1) * 16 : 0) + (q >> 1) * 8;
+        buf_store16_stream(ores, oc < c_out ? (unsigned)row * out_row + oc * 2u : kOobOffset,
+                           u32x4{s0[0], s1[0], s0[1], s1[1]});
     };
     auto flush_all = [&](Origin o) {
         aim_out(o, true);
 #pragma unroll
-        for (int jt = 0; jt < S::JT; ++jt) {
-            flush_a(jt);
-            flush_b(jt);
-        }
+        for (int p = 0; p < kPieces; ++p) flush(p);
     };
 
     char* att0 = lds;
@@ -558,12 +552,10 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
                 constexpr int kParkAt = 1, kFetchAt = 3;
                 if constexpr (kk >= kParkAt && kk < kParkAt + S::kQV) park_q1(q_park, kk - kParkAt);
                 if constexpr (kk >= kFetchAt && kk < kFetchAt + S::kQV) fetch_q1(kk - kFetchAt);
-                // results of tile t-1: two pieces, each parked and written a quarter of the slots later
+                // results of tile t-1, a piece at a time
                 static_assert(kFetchAt + S::kQV <= KCH && S::JT == 2, "slot plan");
-                if constexpr (kk == KCH / 8) flush_a(0);
-                if constexpr (kk == 3 * KCH / 8) flush_b(0);
-                if constexpr (kk == KCH / 2) flush_a(1);
-                if constexpr (kk == 3 * KCH / 4) flush_b(1);
+                if constexpr (kk == KCH / 4) flush(0);
+                if constexpr (kPieces > 1 && kk == 3 * KCH / 4) flush(1);
                 __builtin_amdgcn_sched_barrier(0);
             });
             finish();
