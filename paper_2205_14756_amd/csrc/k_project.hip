@@ -285,10 +285,8 @@ struct WsShape {
     static constexpr int kRow = 160;                     // LDS row pitch of a slab (full-rate reads and writes)
     static constexpr int kSlab = TB * kRow;
     static constexpr int kBuf = NS * kSlab;
-    static constexpr int kStageRow = kChanWave * 2 + 16;
-    static constexpr int kStageWave = 16 * kStageRow;
     static constexpr int kWeightStage = kChanBlock * kRow;        // one slab of the workgroup's weight rows
-    static constexpr int kLds = (2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage) + kWaves * kStageWave;
+    static constexpr int kLds = 2 * kBuf > kWeightStage ? 2 * kBuf : kWeightStage;
     static_assert(TB * 8 == kThreads, "one 16-byte vector per thread and slab");
 };
 
@@ -372,14 +370,12 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
     }
 
     f32x4 acc[S::IO][S::JT];
-    char* stage = lds + S::kLds - (S::kWaves - wave) * S::kStageWave;
     const char* frag_base = lds + x16 * S::kRow + q * 16;
 
     // Results leave one tile late: a tile's accumulators are rounded into `pend`, and during the
-    // NEXT tile's matrix instructions they go 16 tokens x 48 channels at a time through this wave's
-    // staging rows (w), come back as 16-byte words covering whole runs of a token's channels (r) and
-    // are stored (s) -- six small jobs dealt out over the contraction chunks, so the wave issues
-    // matrix instructions all the while.  Before the first tile `dest` is an empty resource.
+    // NEXT tile's matrix instructions they are stored, a pair of fragments at a time -- a few small
+    // jobs dealt out over the contraction chunks, so the wave issues matrix instructions all the
+    // while.  Before the first tile `dest` is an empty resource.
     typedef typename Traits<T>::Frag Frag;
     Frag pend[S::IO][S::JT];
 #pragma unroll
@@ -387,42 +383,39 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_zero<T>();
     auto dest = ep.tile(n_tokens);
-    constexpr int kVecRow = S::kChanWave / 8;                 // 16-byte vectors per token row: 6
-    u32x4 held[2];
-    auto flush_w = [&](int jt) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+    // A fragment is 8 bytes a lane: channels 4q..4q+3 of one 16-channel block for token x16.  Two of
+    // them leave in one 16-byte store: the odd 16-lane groups of one are swapped with the even
+    // groups of the other, after which a lane holds 8 consecutive channels.  Blocks 2m and 2m+1 of
+    // the same 16 tokens pair up (the lane then has channels 32m + 16*(q%2) + 8*(q/2) .. +7 of token
+    // x16); an odd block count leaves the last block, which pairs its two token groups instead
+    // (channels 8*(q/2) .. +7 of token 16*(q%2) + x16).  The lane's store offsets are fixed for the
+    // kernel.
+    constexpr int kPairs = S::IO / 2;                         // channel-block pairs per token group
+    constexpr int kJobs = S::JT * kPairs + (S::IO % 2) * (S::JT / 2);
+    static_assert(S::JT % 2 == 0 && kJobs <= KCH, "one flush job per contraction chunk at most");
+    typename Epilogue::Lane where_pair[kPairs > 0 ? kPairs : 1], where_last;
 #pragma unroll
-        for (int io = 0; io < S::IO; ++io)
-            store_frag<T>(stage + x16 * S::kStageRow + (io * 16 + q * 4) * 2, pend[io][jt]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    auto flush_r = [&]() {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int v = lane + 64 * i;
-            if (v < 16 * kVecRow) held[i] = *(const u32x4*)(stage + (v / kVecRow) * S::kStageRow + (v % kVecRow) * 16);
+    for (int m = 0; m < kPairs; ++m)
+        where_pair[m] = ep.lane(x16, ch0 + 32 * m + (q & 1) * 16 + (q >> 1) * 8, true);
+    where_last = ep.lane((q & 1) * 16 + x16, ch0 + (S::IO - 1) * 16 + (q >> 1) * 8, true);
+    auto flush_job = [&](int job) {
+        u32x2 even, odd;
+        const bool last = job >= S::JT * kPairs;              // the unpaired block, two token groups
+        const int jt = last ? 2 * (job - S::JT * kPairs) : job / (kPairs > 0 ? kPairs : 1);
+        const int m = last ? 0 : job % (kPairs > 0 ? kPairs : 1);
+        if (last) {
+            even = __builtin_bit_cast(u32x2, pend[S::IO - 1][jt]);
+            odd = __builtin_bit_cast(u32x2, pend[S::IO - 1][jt + 1]);
+        } else {
+            even = __builtin_bit_cast(u32x2, pend[2 * m][jt]);
+            odd = __builtin_bit_cast(u32x2, pend[2 * m + (S::IO > 1 ? 1 : 0)][jt]);
         }
+        const u32x2 s0 = __builtin_amdgcn_permlane16_swap(even[0], odd[0], false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane16_swap(even[1], odd[1], false, false);
+        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+        if (last) Epilogue::store(dest, where_last, ch0 + (S::IO - 1) * 16, ch0 + S::IO * 16, jt * 16, v);
+        else Epilogue::store(dest, where_pair[m], ch0 + 32 * m, ch0 + 32 * m + 32, jt * 16, v);
     };
-    typename Epilogue::Lane where[2];      // this lane's two words of a 16-token piece: fixed for the kernel
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int v = lane + 64 * i;
-        where[i] = ep.lane(v / kVecRow, ch0 + (v % kVecRow) * 8, v < 16 * kVecRow);
-    }
-    auto flush_s = [&](int jt) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            if (64 * i < 16 * kVecRow) Epilogue::store(dest, where[i], ch0, ch0 + S::kChanWave, jt * 16, held[i]);
-    };
-    auto flush_job = [&](int job) {       // w0 r0 s0 w1 r1 s1
-        if (job % 3 == 0) flush_w(job / 3);
-        else if (job % 3 == 1) flush_r();
-        else flush_s(job / 3);
-    };
-    static_assert(S::JT == 2, "six flush jobs");
 
     park(lds);
     __syncthreads();
@@ -452,10 +445,10 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
 #pragma unroll
                 for (int jt = 0; jt < S::JT; ++jt)
                     acc[io][jt] = Traits<T>::mma_vec(acc[io][jt], wf[io][kk], bf[kk % 3][jt]);
-            // the previous tile's results: job j rides in chunk j*KCH/6
-            static_for<0, 6>([&](auto job_c) {
+            // the previous tile's results: job j rides in the middle of the j-th of kJobs runs of chunks
+            static_for<0, kJobs>([&](auto job_c) {
                 constexpr int job = decltype(job_c)::value;
-                if constexpr (job * KCH / 6 == kk) flush_job(job);
+                if constexpr ((2 * job + 1) * KCH / (2 * kJobs) == kk) flush_job(job);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -469,7 +462,7 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
         cur ^= 1;
     }
 #pragma unroll
-    for (int job = 0; job < 6; ++job) flush_job(job);
+    for (int job = 0; job < kJobs; ++job) flush_job(job);
 }
 
 template <class T, int KCH, class Epilogue>
