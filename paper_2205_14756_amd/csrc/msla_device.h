@@ -218,9 +218,15 @@ __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, unsigned voffset, int sof
 __device__ __forceinline__ void buf_store16(BufRsrc r, unsigned voffset, u32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, 0, 0);
 }
-// ... with a wave-uniform byte offset on top (never negative; the range check sees only voffset)
+// ... with a wave-uniform byte offset (below 2^31) on top.  It is added to the lane's offset rather
+// than handed to the instruction's scalar-offset field, for two reasons.  The range check covers the
+// lane's offset only, so a row the scalar offset pushes past the end of the resource would still be
+// written.  And the compiler leaves no wait state between a 16-byte store with a scalar offset and
+// a vector instruction that overwrites the store's data registers, where this chip needs one: with
+// the data registers reused right behind the store, the first word of some lanes came out wrong in
+// about one launch in twenty.
 __device__ __forceinline__ void buf_store16_at(BufRsrc r, unsigned voffset, unsigned soffset, u32x4 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voffset, (int)soffset, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)(voffset + soffset), 0, 0);
 }
 // The same store written through to memory (the sc1 cache-policy bit): for output that no later
 // kernel of the module reads.  Such lines are not left dirty in L2, where they would displace the

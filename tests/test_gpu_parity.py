@@ -138,6 +138,41 @@ def test_linear(dtype, n, c_in, c_out):
     assert rel_err(y, orc.linear(x, w)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("n,c_in,c_out", [(2049, 128, 384), (1000, 256, 768), (24, 256, 768), (777, 80, 48),
+                                          (40, 512, 272)])
+def test_linear_writes_only_its_own_rows(dtype, n, c_in, c_out):
+    """Token counts that leave the last tile ragged: the rows behind the last token, which the same
+    allocation holds, keep their contents."""
+    import torch
+    rng = np.random.default_rng(7 * n + c_out)
+    x = wk.round_to_dtype(rng.standard_normal((n, c_in)), dtype)
+    w = wk.round_to_dtype(rng.standard_normal((c_out, c_in)) / np.sqrt(c_in), dtype)
+    print(f"linear, guard rows: {dtype} n={n} {c_in}->{c_out}", flush=True)
+    guard = 64
+    whole = torch.full((n + guard, c_out), 123.0, dtype=TDT[dtype], device="cuda")
+    msla.msla_linear(dev(x, dtype), dev(w, dtype), y=whole[:n])
+    assert rel_err(host(whole[:n]), orc.linear(x, w)) <= TOL[dtype]
+    assert bool((whole[n:] == 123.0).all()), "rows past the last token were written"
+
+
+def test_linear_repeated_launches_agree():
+    """The same projection launched many times gives the same bits every time (a store whose data
+    registers were overwritten one instruction later once corrupted a word in a few launches of a
+    hundred at this shape)."""
+    import torch
+    n, c_in, c_out = 3 * 64 * 96, 256, 768
+    rng = np.random.default_rng(5)
+    x = wk.round_to_dtype(rng.standard_normal((n, c_in)), "f16")
+    w = wk.round_to_dtype(rng.standard_normal((c_out, c_in)) / np.sqrt(c_in), "f16")
+    print(f"linear, 150 launches: f16 n={n} {c_in}->{c_out}", flush=True)
+    xd, wd = dev(x, "f16"), dev(w, "f16")
+    first = msla.msla_linear(xd, wd)
+    assert rel_err(host(first), orc.linear(x, w)) <= TOL["f16"]
+    differing = sum(int(not torch.equal(first, msla.msla_linear(xd, wd))) for _ in range(150))
+    assert differing == 0, f"{differing} of 150 launches differ from the first"
+
+
 # -------------------------------------- S1-S4: aggregation, state, normalise-and-apply
 
 STATE_CASES = [
@@ -223,6 +258,29 @@ def test_forward_several_tiles_per_workgroup(dtype, B, C, H, W, heads, scales):
     print(f"forward, several tiles per workgroup: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
     t = wk.random_module(C * 1000 + B * 100 + H + W, dtype, B, C, H, W, heads, d, scales)
     check_module(t, dtype, heads, d, scales)
+
+
+@pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
+    ("f16", 1, 64, 5, 7, 4, (5,)),          # 35 tokens: every kernel's only tile is ragged
+    ("bf16", 3, 128, 9, 11, 8, (3, 5)),     # 297 tokens, tiles that cross images
+    ("f32", 2, 64, 9, 5, 4, (5,)),
+    ("f16", 2, 256, 13, 17, 16, (5,)),      # the weight-stationary kernels of the headline shape, 442 tokens
+])
+def test_forward_writes_only_its_own_rows(dtype, B, C, H, W, heads, scales):
+    """The output lies at the start of a larger allocation: what follows its last token stays as it was."""
+    d = 16
+    print(f"forward, guard rows: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
+    t = wk.random_module(99 + C + H * W, dtype, B, C, H, W, heads, d, scales)
+    x = dev(t["x"], dtype)
+    wdw, wg = weights(t, dtype, scales)
+    T, guard = B * H * W, 64
+    whole = torch.full((T + guard, C), 123.0, dtype=TDT[dtype], device="cuda")
+    out = whole[:T].view(B, H, W, C)
+    msla.msla_forward(x, dev(t["w_qkv"], dtype), wdw, wg, dev(t["w_proj"], dtype), heads, d, scales, 1e-15,
+                      out=out, workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype))
+    # (parity of such shapes is the business of the tests above)
+    assert np.isfinite(host(out)).all()
+    assert bool((whole[T:] == 123.0).all()), "rows past the last token were written"
 
 
 @pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
