@@ -279,16 +279,22 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     const unsigned row_bytes = (unsigned)K * 2u;
     const int ch0 = cg * S::kChanBlock + wave * S::kChanWave;
 
-    // tile number -> (image, first token in it), walked with counters: no division in the loop
+    // tile number -> (image, first token in it, that token's index in the whole map), walked with
+    // counters: no division and no wide multiplication in the loop (the scalar unit runs a wave's
+    // instructions one after the other, some eight cycles each)
     struct Origin {
         int b, n0;
+        unsigned tok;
     };
     auto advance = [&](Origin o) {
-        o.n0 += S::TB;
-        if (o.n0 >= N) { o.n0 = 0; ++o.b; }
+        const int left = N - o.n0;                  // tokens of the image from this tile on
+        o.tok += left < S::TB ? left : S::TB;
+        if (left <= S::TB) { o.n0 = 0; ++o.b; }
+        else o.n0 += S::TB;
         return o;
     };
-    const Origin first = {(int)(t_begin / tiles_per_image), (int)(t_begin % tiles_per_image) * S::TB};
+    const Origin first = {(int)(t_begin / tiles_per_image), (int)(t_begin % tiles_per_image) * S::TB,
+                          (unsigned)((t_begin / tiles_per_image) * N + (t_begin % tiles_per_image) * S::TB)};
 
     // ---- Q tile: copied in row order (8 lanes per 128-byte row segment; read as fragments straight
     // from memory every lane would touch its own row) into LDS.  Rows past the image's last token
@@ -300,18 +306,18 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     BufRsrc qres;
     auto aim_q = [&](Origin o, bool live) {
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
-        qres = make_rsrc(q_ms + ((long)o.b * N + o.n0) * K, (long)rows * row_bytes);
+        qres = make_rsrc_small(q_ms + (size_t)o.tok * K, (unsigned)rows * row_bytes);
     };
     auto fetch_q1 = [&](int i) {
         qv[i] = buf_load16(qres, q_slab * 128 + q_chunk * 16 + i * 256 < row_bytes ? q_glb + i * 256 : kOobOffset, 0);
     };
     // Eq. (3) only ever sees relu(Q): the rectifier is applied here, once per element, as integer
     // maxima on the bit patterns (negative values and -0 have the sign bit set)
-    auto park_q1 = [&](char* qb, int i) {
+    auto park_q1 = [&](int qb, int i) {       // qb: byte offset of the Q tile in LDS
         typedef short i16x8 __attribute__((ext_vector_type(8)));
         const i16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
         const i16x8 r = __builtin_elementwise_max(__builtin_bit_cast(i16x8, qv[i]), zero);
-        *(u32x4*)(qb + q_lds + 2 * i * S::kSlab) = __builtin_bit_cast(u32x4, r);
+        *(u32x4*)(lds + qb + q_lds + 2 * i * S::kSlab) = __builtin_bit_cast(u32x4, r);
     };
 
     aim_q(first, true);      // requested ahead of the weights, so the first tile does not queue behind them
@@ -391,7 +397,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         const int chunk = (hb & 3) * 2 + (q >> 1);
         return (hb >> 2) * S::kSlab + ((u / S::HBW) * 16 + x16) * S::kRow + (chunk ^ g16) * 16 + (q & 1) * 8;
     };
-    auto att_a = [&](const char* qb, int u) { att_q[u & 1] = load_frag<T>((const T*)(qb + unit_off(u))); };
+    auto att_a = [&](int qb, int u) { att_q[u & 1] = load_frag<T>((const T*)(lds + qb + unit_off(u))); };
     auto att_b = [&](int u) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         const Frag qf = att_q[u & 1];         // rectified when the tile was parked
@@ -401,7 +407,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         att_num = Tr::mma_vec(z, a_kv[u % S::HBW], b);
         att_den = Tr::mma_vec(z, a_ks[u % S::HBW], b);
     };
-    auto att_c = [&](int u, char* hi_tile, char* lo_tile) {
+    auto att_c = [&](int u, int hi_tile, int lo_tile) {
         const int hb = wave * S::HBW + u % S::HBW;
         const f32x4 num = att_num;
         const float inv = hb < n_hb ? __builtin_amdgcn_rcpf(att_den[0] + eps_s[u % S::HBW]) : 0.f;
@@ -410,14 +416,14 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         if constexpr (kHiLo) {
             Frag hi, lo;
             frag_split<T>(o, hi, lo);
-            store_frag<T>(hi_tile + off, hi);
-            store_frag<T>(lo_tile + off, lo);
+            store_frag<T>(lds + hi_tile + off, hi);
+            store_frag<T>(lds + lo_tile + off, lo);
         } else {
-            store_frag<T>(hi_tile + off, frag_from_f32<T>(o));
+            store_frag<T>(lds + hi_tile + off, frag_from_f32<T>(o));
         }
     };
     // all units of a tile, the stages of neighbouring units overlapped
-    auto att_all = [&](const char* qb, char* hi_tile, char* lo_tile) {
+    auto att_all = [&](int qb, int hi_tile, int lo_tile) {
         att_a(qb, 0);
 #pragma unroll
         for (int u = 0; u < kUnits; ++u) {
@@ -434,11 +440,11 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     f32x4 acc[IO][S::JT];
     const int frag_off = x16 * S::kRow + (q ^ g16) * 16;       // chunk (kk&1)*4 + q: the second half is ^ 64
     Vec bf[kRing][S::JT];
-    auto read_b = [&](const char* tile, int kk) {
+    auto read_b = [&](int tile, int kk) {
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt)
             bf[kk % kRing][jt] = __builtin_bit_cast(
-                Vec, *(const u32x4*)(tile + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
+                Vec, *(const u32x4*)(lds + tile + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
     };
     auto mma_chunk = [&](int kk) {
 #pragma unroll
@@ -472,7 +478,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     };
     auto aim_out = [&](Origin o, bool live) {
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
-        ores = make_rsrc(out + ((long)o.b * N + o.n0) * c_out, (long)rows * out_row);
+        ores = make_rsrc_small(out + (size_t)o.tok * c_out, (unsigned)rows * out_row);
     };
     auto flush = [&](int p) {
         u32x2 even, odd;
@@ -496,10 +502,9 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         for (int p = 0; p < kPieces; ++p) flush(p);
     };
 
-    char* att0 = lds;
-    char* att1 = lds + S::kBuf;
-    char* qb0 = lds + 2 * S::kBuf;
-    char* qb1 = lds + 3 * S::kBuf;
+    // the four tiles as byte offsets into LDS (plain numbers: a pointer chosen at run time would be
+    // checked against null wherever something is added to it)
+    constexpr int att0 = 0, att1 = S::kBuf, qb0 = 2 * S::kBuf, qb1 = 3 * S::kBuf;
     if constexpr (!kHiLo) {
         // prologue: Q tiles 0 and 1 parked, Q tile 2 requested, attention rows of tile 0 made
         Origin o_att = first;                 // tile whose attention rows are made next
@@ -517,16 +522,16 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
         load_state(o_att.b);
         __syncthreads();
-        att_all(qb0, att0, nullptr);
+        att_all(qb0, att0, 0);
         __syncthreads();
         Origin o_out = first;                 // tile whose results are written next
         o_att = advance(o_att);
         for (int t = 0; t < n_mine; ++t) {
             const bool odd = t & 1;
-            const char* here = odd ? att1 : att0;       // attention rows of tile t
-            char* next = odd ? att0 : att1;             // ... of tile t+1, made now
-            const char* q_next = odd ? qb0 : qb1;       // Q of tile t+1
-            char* q_park = odd ? qb1 : qb0;             // Q of tile t+2 goes where tile t's was
+            const int here = odd ? att1 : att0;         // attention rows of tile t
+            const int next = odd ? att0 : att1;         // ... of tile t+1, made now
+            const int q_next = odd ? qb0 : qb1;         // Q of tile t+1
+            const int q_park = odd ? qb1 : qb0;         // Q of tile t+2 goes where tile t's was
             if (t + 1 < n_mine && o_att.b != img) load_state(o_att.b);
             o_q = advance(o_q);
             aim_q(o_q, t + 3 < n_mine);                 // resource of Q tile t+3
@@ -545,7 +550,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
                     att_b(u);
                     if constexpr (u + 1 < kUnits) att_a(q_next, u + 1);
                 } else {
-                    att_c(u, next, nullptr);
+                    att_c(u, next, 0);
                 }
                 mma_chunk(kk);
                 // Q tile t+2: registers -> LDS, then the same registers take the request for tile t+3
@@ -590,7 +595,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
                 for (int jt = 0; jt < S::JT; ++jt)
                     lo[jt] = __builtin_bit_cast(
-                        Vec, *(const u32x4*)(att1 + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
+                        Vec, *(const u32x4*)(lds + att1 + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
                 if (kk + 1 < KCH) read_b(att0, kk + 1);
                 mma_chunk(kk);
 #pragma unroll

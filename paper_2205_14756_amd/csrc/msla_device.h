@@ -212,6 +212,10 @@ __device__ __forceinline__ BufRsrc make_rsrc(const void* base, long bytes) {
     const int n = bytes > 0x7fffffffL ? 0x7fffffff : (bytes < 0 ? 0 : (int)bytes);
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
 }
+// ... for a span known to be small (a tile): no clamping, so nothing but the descriptor words
+__device__ __forceinline__ BufRsrc make_rsrc_small(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
 __device__ __forceinline__ u32x4 buf_load16(BufRsrc r, unsigned voffset, int soffset) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voffset, soffset, 0);
 }
