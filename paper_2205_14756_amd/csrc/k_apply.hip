@@ -306,7 +306,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     BufRsrc qres;
     auto aim_q = [&](Origin o, bool live) {
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
-        qres = make_rsrc_small(q_ms + (size_t)o.tok * K, (unsigned)rows * row_bytes);
+        qres = make_rsrc_small(q_ms + (size_t)o.tok * (unsigned)K, (unsigned)rows * row_bytes);
     };
     auto fetch_q1 = [&](int i) {
         qv[i] = buf_load16(qres, q_slab * 128 + q_chunk * 16 + i * 256 < row_bytes ? q_glb + i * 256 : kOobOffset, 0);
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     };
     auto aim_out = [&](Origin o, bool live) {
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
-        ores = make_rsrc_small(out + (size_t)o.tok * c_out, (unsigned)rows * out_row);
+        ores = make_rsrc_small(out + (size_t)o.tok * (unsigned)c_out, (unsigned)rows * out_row);
     };
     auto flush = [&](int p) {
         u32x2 even, odd;
