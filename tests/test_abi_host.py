@@ -136,3 +136,14 @@ def test_product_path_does_not_touch_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "msla_oracle" not in text, os.path.join(dirpath, f)
                 assert not re.search(r"^\s*(import|from)\s+\S*oracle", text, flags=re.M), os.path.join(dirpath, f)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; asked for more, the bench says so and does not start."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+    assert not any(line.startswith("{") for line in r.stdout.splitlines())
