@@ -48,6 +48,8 @@ struct PlainDest {
         const long rb = (long)c_out * (long)sizeof(T);
         return Tile{make_rsrc(y + tok0 * c_out, (n_tokens - tok0) * rb), (unsigned)rb, c_out};
     }
+    // a writer that drops everything (what the pipelined epilogue holds before its first tile)
+    __device__ __forceinline__ Tile none() const { return Tile{make_rsrc(y, 0), 0u, c_out}; }
     // A lane's part of a store that does not change from tile to tile: its byte offset inside a
     // group of 16 token rows (beyond every resource where the lane has nothing to write).
     struct Lane {
@@ -62,26 +64,35 @@ struct PlainDest {
 };
 
 // Q/K/V projection with split destinations.  The kernel walks the output channels in DESTINATION
-// order -- first the Ct channels of Q (head-major), then the 2*Ct channels of K|V as they lie in
-// kv_raw -- so a tile's channels of one token are one contiguous run in memory; row_of maps such a
-// channel to its row (h*3 + t)*16 + e of w_qkv.
+// order -- first the Ct channels of Q (head-major), then the 2*Ct channels of K|V, head by head --
+// so a tile's channels of one token are few contiguous runs in memory; row_of maps such a channel
+// to its row (h*3 + t)*16 + e of w_qkv.
+// The K|V map holds, for token n and head h, 32 contiguous channels (K then V) at
+//   kv_raw + n * kv_tok_stride + h * kv_head_stride          (elements)
+// -- token-major (2*Ct, 32) or head-major (32, padded token count * 32).  Head-major is what the
+// aggregation pass reads best (a head's tokens are contiguous); its token count is padded to whole
+// tiles, so the rows of a ragged last tile fall into the padding.  kv_span is the size of the map;
+// a head-major map must stay below 2^31 bytes (32-bit offsets inside a tile's resource).
 template <class T>
 struct QkvSplitDest {
     T* q_ms;
     long q_ms_stride;
     T* kv_raw;
-    long kv_stride;
+    long kv_tok_stride, kv_head_stride, kv_span;
     long n_tokens;
     int Ct;
     struct Tile {
         BufRsrc q, kv;
-        unsigned q_row_bytes, kv_row_bytes;
+        unsigned q_row_bytes, kv_row_bytes, kv_head_bytes;
         int Ct;
+        __device__ __forceinline__ unsigned kv_off(int row, int vc) const {
+            const int v2 = vc - Ct;
+            return (unsigned)row * kv_row_bytes + (unsigned)(v2 >> 5) * kv_head_bytes + (unsigned)(v2 & 31) * (unsigned)sizeof(T);
+        }
         __device__ __forceinline__ void store(int piece0, int piece_end, int row, int vc, u32x4 v) const {
             constexpr unsigned sz = (unsigned)sizeof(T);
             if (piece0 < Ct) buf_store16(q, vc < Ct ? row * q_row_bytes + vc * sz : kOobOffset, v);
-            if (piece_end > Ct)
-                buf_store16(kv, (vc >= Ct && vc < 3 * Ct) ? row * kv_row_bytes + (vc - Ct) * sz : kOobOffset, v);
+            if (piece_end > Ct) buf_store16(kv, (vc >= Ct && vc < 3 * Ct) ? kv_off(row, vc) : kOobOffset, v);
         }
     };
     __device__ __forceinline__ int row_of(int vc) const {
@@ -90,18 +101,25 @@ struct QkvSplitDest {
         return (v2 >> 5) * 48 + 16 + (v2 & 31);
     }
     __device__ __forceinline__ Tile tile(long tok0) const {
-        const long qb = q_ms_stride * (long)sizeof(T), kb = kv_stride * (long)sizeof(T);
+        const long qb = q_ms_stride * (long)sizeof(T), kb = kv_tok_stride * (long)sizeof(T);
         return Tile{make_rsrc(q_ms + tok0 * q_ms_stride, (n_tokens - tok0) * qb),
-                    make_rsrc(kv_raw + tok0 * kv_stride, (n_tokens - tok0) * kb), (unsigned)qb, (unsigned)kb, Ct};
+                    make_rsrc(kv_raw + tok0 * kv_tok_stride, (kv_span - tok0 * kv_tok_stride) * (long)sizeof(T)),
+                    (unsigned)qb, (unsigned)kb, (unsigned)(kv_head_stride * sizeof(T)), Ct};
+    }
+    __device__ __forceinline__ Tile none() const {
+        return Tile{make_rsrc(q_ms, 0), make_rsrc(kv_raw, 0), 0u, 0u, 0u, Ct};
     }
     struct Lane {
         unsigned q, kv;
     };
     __device__ __forceinline__ Lane lane(int row, int vc, bool live) const {
         constexpr unsigned sz = (unsigned)sizeof(T);
-        const unsigned qb = (unsigned)(q_ms_stride * sizeof(T)), kb = (unsigned)(kv_stride * sizeof(T));
+        const unsigned qb = (unsigned)(q_ms_stride * sizeof(T)), kb = (unsigned)(kv_tok_stride * sizeof(T));
+        const unsigned hb = (unsigned)(kv_head_stride * sizeof(T));
+        const int v2 = vc - Ct;
         return Lane{live && vc < Ct ? (unsigned)row * qb + vc * sz : kOobOffset,
-                    live && vc >= Ct && vc < 3 * Ct ? (unsigned)row * kb + (vc - Ct) * sz : kOobOffset};
+                    live && vc >= Ct && vc < 3 * Ct ? (unsigned)row * kb + (unsigned)(v2 >> 5) * hb + (unsigned)(v2 & 31) * sz
+                                                   : kOobOffset};
     }
     // piece0 .. piece_end: the wave's channel range, which tells (wave-uniformly) which maps it touches
     static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int piece0, int piece_end, int row0, u32x4 v) {
@@ -382,7 +400,7 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
     for (int io = 0; io < S::IO; ++io)
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_zero<T>();
-    auto dest = ep.tile(n_tokens);
+    auto dest = ep.none();
     // A fragment is 8 bytes a lane: channels 4q..4q+3 of one 16-channel block for token x16.  Two of
     // them leave in one 16-byte store: the odd 16-lane groups of one are swapped with the even
     // groups of the other, after which a lane holds 8 consecutive channels.  Blocks 2m and 2m+1 of
@@ -532,16 +550,19 @@ hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_t
 }
 
 hipError_t launch_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
-                              void* kv_raw, long n_tokens, int c_in, int heads, hipStream_t stream) {
+                              void* kv_raw, long kv_tok_stride, long kv_head_stride, long kv_span,
+                              long n_tokens, int c_in, int heads, hipStream_t stream) {
     const int c_out = 3 * heads * 16;
-    const long kv_stride = 2L * heads * 16;
     switch (dt) {
         case 0: return run_project<float>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<float>{(float*)q_ms, q_ms_stride, (float*)kv_raw, kv_stride, n_tokens, heads * 16}, stream);
+                    QkvSplitDest<float>{(float*)q_ms, q_ms_stride, (float*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
+                                           n_tokens, heads * 16}, stream);
         case 1: return run_project<_Float16>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<_Float16>{(_Float16*)q_ms, q_ms_stride, (_Float16*)kv_raw, kv_stride, n_tokens, heads * 16}, stream);
+                    QkvSplitDest<_Float16>{(_Float16*)q_ms, q_ms_stride, (_Float16*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
+                                           n_tokens, heads * 16}, stream);
         case 2: return run_project<__bf16>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<__bf16>{(__bf16*)q_ms, q_ms_stride, (__bf16*)kv_raw, kv_stride, n_tokens, heads * 16}, stream);
+                    QkvSplitDest<__bf16>{(__bf16*)q_ms, q_ms_stride, (__bf16*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
+                                           n_tokens, heads * 16}, stream);
     }
     return hipErrorInvalidValue;
 }

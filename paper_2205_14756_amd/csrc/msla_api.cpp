@@ -75,13 +75,23 @@ struct Workspace {
     size_t q_ms, kv_raw, partials, kv32, kvfrag, kvscale, total;
 };
 
+long kv_padded_tokens(const Shape& s) { return (s.T + 31) / 32 * 32; }
+
+// The forward pass keeps K|V head-major ([head][token][K 16 | V 16]) when the matrix-core aggregation
+// kernel will read it -- a head's tokens are then contiguous, which that kernel's loads like (-2 us
+// on the headline workload) -- and the map fits 32-bit byte offsets; token-major otherwise.
+bool kv_head_major(const Shape& s, msla_dtype dt) {
+    return dt != MSLA_F32 && s.n_scales > 0 && (size_t)kv_padded_tokens(s) * 2 * s.Ct * elem_size(dt) < (1ull << 31);
+}
+
 Workspace carve(const Shape& s, msla_dtype dt) {
     const size_t e = elem_size(dt);
     const size_t n_states = (size_t)s.B * s.S * s.heads;
     Workspace w;
     size_t off = 0;
     w.q_ms = off;     off += align_up((size_t)s.T * s.S * s.Ct * e);
-    w.kv_raw = off;   off += align_up((size_t)s.T * 2 * s.Ct * e);
+    // (token count rounded up to whole projection tiles: the head-major form of this map pads each head)
+    w.kv_raw = off;   off += align_up((size_t)kv_padded_tokens(s) * 2 * s.Ct * e);
     w.partials = off; off += align_up(n_states * s.nchunks * 272 * sizeof(float));
     w.kv32 = off;     off += align_up(n_states * 272 * sizeof(float));
     w.kvfrag = off;   off += align_up(n_states * 2048);
@@ -233,11 +243,16 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
         out_tok = kv_raw;
     }
     // Q/K/V projection; raw Q lands in the branch-0 columns of the multi-scale Q map
-    if (msla::launch_qkv_project((int)dt, x_tok, w_qkv, q_ms, q_ms_ts, kv_raw, s.T, C, s.heads, hs) != hipSuccess)
+    const bool hm = kv_head_major(s, dt);
+    const long kv_ts = hm ? 32 : 2L * s.Ct;                       // elements from token to token
+    const long kv_hs = hm ? kv_padded_tokens(s) * 32 : 32;        // ... from head to head
+    const long kv_span = hm ? kv_padded_tokens(s) * 2 * s.Ct : s.T * 2 * s.Ct;
+    if (msla::launch_qkv_project((int)dt, x_tok, w_qkv, q_ms, q_ms_ts, kv_raw, kv_ts, kv_hs, kv_span, s.T, C, s.heads,
+                                 hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (!mark(1)) return MSLA_ERR_LAUNCH;
     // aggregation + Eq. (3) state
-    st = run_state(s, dt, q_ms, q_ms_ts, 16, kv_raw, 2L * s.Ct, 32, kv_raw + 16 * e, 2L * s.Ct, 32, w_dw, w_gpw,
+    st = run_state(s, dt, q_ms, q_ms_ts, 16, kv_raw, kv_ts, (int)kv_hs, kv_raw + 16 * e, kv_ts, (int)kv_hs, w_dw, w_gpw,
                    ws, wo, q_ms, /*copy_raw_q=*/0, hs, events ? events[2] : nullptr);
     if (st != MSLA_OK) return st;
     if (!mark(3)) return MSLA_ERR_LAUNCH;

@@ -13,9 +13,13 @@ hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_t
 
 // The Q/K/V projection with a split destination: output channel (h*3+t)*16+e goes to
 //   t = 0: q_ms[n * q_ms_stride + h*16 + e]       (branch-0 columns of the multi-scale Q map)
-//   t > 0: kv_raw[n * 2*Ct + h*32 + (t-1)*16 + e]
+//   t > 0: kv_raw[n * kv_tok_stride + h * kv_head_stride + (t-1)*16 + e]
+// with (kv_tok_stride, kv_head_stride) = (2*Ct, 32) for a token-major K|V map or (32, P*32) for a
+// head-major one whose P >= n_tokens is a multiple of 32 (rows of a ragged last tile fall into the
+// padding); kv_span = elements of the whole map, below 2^30 when head-major.
 hipError_t launch_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
-                              void* kv_raw, long n_tokens, int c_in, int heads, hipStream_t stream);
+                              void* kv_raw, long kv_tok_stride, long kv_head_stride, long kv_span,
+                              long n_tokens, int c_in, int heads, hipStream_t stream);
 
 struct AggregateArgs {
     // raw Q, K, V maps: element (token n, head h, channel e) of map m lives at
