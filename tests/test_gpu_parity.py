@@ -267,7 +267,8 @@ def test_forward_several_tiles_per_workgroup(dtype, B, C, H, W, heads, scales):
     ("f16", 2, 256, 13, 17, 16, (5,)),      # the weight-stationary kernels of the headline shape, 442 tokens
 ])
 def test_forward_writes_only_its_own_rows(dtype, B, C, H, W, heads, scales):
-    """The output lies at the start of a larger allocation: what follows its last token stays as it was."""
+    """The output and the workspace each lie at the start of a larger allocation: what follows the last
+    token, and the bytes behind the size msla_workspace_bytes reports, stay as they were."""
     d = 16
     print(f"forward, guard rows: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
     t = wk.random_module(99 + C + H * W, dtype, B, C, H, W, heads, d, scales)
@@ -276,8 +277,11 @@ def test_forward_writes_only_its_own_rows(dtype, B, C, H, W, heads, scales):
     T, guard = B * H * W, 64
     whole = torch.full((T + guard, C), 123.0, dtype=TDT[dtype], device="cuda")
     out = whole[:T].view(B, H, W, C)
+    n_ws = msla.msla_workspace_bytes(B, C, H, W, heads, d, scales, TDT[dtype])
+    ws_whole = torch.full((n_ws + 4096,), 0xFF, dtype=torch.uint8, device="cuda")
     msla.msla_forward(x, dev(t["w_qkv"], dtype), wdw, wg, dev(t["w_proj"], dtype), heads, d, scales, 1e-15,
-                      out=out, workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype))
+                      out=out, workspace=ws_whole[:n_ws])
+    assert bool((ws_whole[n_ws:] == 0xFF).all()), "bytes past the workspace were written"
     # (parity of such shapes is the business of the tests above)
     assert np.isfinite(host(out)).all()
     assert bool((whole[T:] == 123.0).all()), "rows past the last token were written"
