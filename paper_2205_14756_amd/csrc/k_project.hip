@@ -58,7 +58,9 @@ struct PlainDest {
     __device__ __forceinline__ Lane lane(int row, int oc, bool live) const {
         return Lane{live && oc < c_out ? (unsigned)row * (unsigned)(c_out * sizeof(T)) + oc * (unsigned)sizeof(T) : kOobOffset};
     }
-    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int, int, int row0, u32x4 v) {
+    // (piece0 .. piece_end: the channels the storing wave covers; local0: the stored piece's first
+    // channel counted from the wave's first -- both unused here)
+    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int, int, int, int row0, u32x4 v) {
         buf_store16_at(t.y, l.off, (unsigned)row0 * t.row_bytes, v);
     }
 };
@@ -85,6 +87,7 @@ struct QkvSplitDest {
         BufRsrc q, kv;
         unsigned q_row_bytes, kv_row_bytes, kv_head_bytes;
         int Ct;
+        int rows;       // tokens from this tile's first to the map's last
         __device__ __forceinline__ unsigned kv_off(int row, int vc) const {
             const int v2 = vc - Ct;
             return (unsigned)row * kv_row_bytes + (unsigned)(v2 >> 5) * kv_head_bytes + (unsigned)(v2 & 31) * (unsigned)sizeof(T);
@@ -92,7 +95,8 @@ struct QkvSplitDest {
         __device__ __forceinline__ void store(int piece0, int piece_end, int row, int vc, u32x4 v) const {
             constexpr unsigned sz = (unsigned)sizeof(T);
             if (piece0 < Ct) buf_store16(q, vc < Ct ? row * q_row_bytes + vc * sz : kOobOffset, v);
-            if (piece_end > Ct) buf_store16(kv, (vc >= Ct && vc < 3 * Ct) ? kv_off(row, vc) : kOobOffset, v);
+            // (a row past the last token would not leave a head-major map's resource: it is masked here)
+            if (piece_end > Ct) buf_store16(kv, (vc >= Ct && vc < 3 * Ct && row < rows) ? kv_off(row, vc) : kOobOffset, v);
         }
     };
     __device__ __forceinline__ int row_of(int vc) const {
@@ -104,10 +108,11 @@ struct QkvSplitDest {
         const long qb = q_ms_stride * (long)sizeof(T), kb = kv_tok_stride * (long)sizeof(T);
         return Tile{make_rsrc(q_ms + tok0 * q_ms_stride, (n_tokens - tok0) * qb),
                     make_rsrc(kv_raw + tok0 * kv_tok_stride, (kv_span - tok0 * kv_tok_stride) * (long)sizeof(T)),
-                    (unsigned)qb, (unsigned)kb, (unsigned)(kv_head_stride * sizeof(T)), Ct};
+                    (unsigned)qb, (unsigned)kb, (unsigned)(kv_head_stride * sizeof(T)), Ct,
+                    (int)(n_tokens - tok0 < 0x7fffffffL ? n_tokens - tok0 : 0x7fffffffL)};
     }
     __device__ __forceinline__ Tile none() const {
-        return Tile{make_rsrc(q_ms, 0), make_rsrc(kv_raw, 0), 0u, 0u, 0u, Ct};
+        return Tile{make_rsrc(q_ms, 0), make_rsrc(kv_raw, 0), 0u, 0u, 0u, Ct, 0};
     }
     struct Lane {
         unsigned q, kv;
@@ -122,9 +127,56 @@ struct QkvSplitDest {
                                                    : kOobOffset};
     }
     // piece0 .. piece_end: the wave's channel range, which tells (wave-uniformly) which maps it touches
-    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int piece0, int piece_end, int row0, u32x4 v) {
+    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int piece0, int piece_end, int, int row0, u32x4 v) {
         if (piece0 < t.Ct) buf_store16_at(t.q, l.q, (unsigned)row0 * t.q_row_bytes, v);
         if (piece_end > t.Ct) buf_store16_at(t.kv, l.kv, (unsigned)row0 * t.kv_row_bytes, v);
+    }
+};
+
+// The same destinations for the weight-stationary kernel with 48 channels a wave: a wave is one
+// head, and its three 16-channel blocks are that head's K, V and Q in this order.  K and V then
+// pair up into one store of a token's 64-byte K|V run -- with a head-major map sixteen tokens' runs
+// are one contiguous kilobyte -- the Q block pairs its two token groups, and which map a store
+// goes to is known when the kernel is compiled: no branches, one offset a lane.
+template <class T>
+struct QkvHeadDest {
+    T* q_ms;
+    long q_ms_stride;
+    T* kv_raw;
+    long kv_tok_stride, kv_head_stride, kv_span;
+    long n_tokens;
+    int Ct;
+    struct Tile {
+        BufRsrc q, kv;
+        unsigned q_row_bytes, kv_row_bytes;
+    };
+    // channel vc of the walk = (head vc / 48, r = vc % 48): r < 32 is K|V channel r, else Q channel r - 32
+    __device__ __forceinline__ int row_of(int vc) const {
+        const int head = vc / 48, r = vc - head * 48;
+        return head * 48 + (r < 32 ? 16 + r : r - 32);
+    }
+    __device__ __forceinline__ Tile tile(long tok0) const {
+        const long qb = q_ms_stride * (long)sizeof(T), kb = kv_tok_stride * (long)sizeof(T);
+        return Tile{make_rsrc(q_ms + tok0 * q_ms_stride, (n_tokens - tok0) * qb),
+                    make_rsrc(kv_raw + tok0 * kv_tok_stride, (kv_span - tok0 * kv_tok_stride) * (long)sizeof(T)),
+                    (unsigned)qb, (unsigned)kb};
+    }
+    __device__ __forceinline__ Tile none() const { return Tile{make_rsrc(q_ms, 0), make_rsrc(kv_raw, 0), 0u, 0u}; }
+    struct Lane {
+        unsigned off;
+    };
+    __device__ __forceinline__ Lane lane(int row, int vc, bool live) const {
+        constexpr unsigned sz = (unsigned)sizeof(T);
+        const int head = vc / 48, r = vc - head * 48;
+        if (!live || vc >= 3 * Ct) return Lane{kOobOffset};
+        if (r < 32)
+            return Lane{(unsigned)row * (unsigned)(kv_tok_stride * sizeof(T)) +
+                        (unsigned)head * (unsigned)(kv_head_stride * sizeof(T)) + (unsigned)r * sz};
+        return Lane{(unsigned)row * (unsigned)(q_ms_stride * sizeof(T)) + (unsigned)(head * 16 + r - 32) * sz};
+    }
+    static __device__ __forceinline__ void store(const Tile& t, const Lane& l, int, int, int local0, int row0, u32x4 v) {
+        if (local0 < 32) buf_store16_at(t.kv, l.off, (unsigned)row0 * t.kv_row_bytes, v);
+        else buf_store16_at(t.q, l.off, (unsigned)row0 * t.q_row_bytes, v);
     }
 };
 
@@ -431,8 +483,8 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
         const u32x2 s0 = __builtin_amdgcn_permlane16_swap(even[0], odd[0], false, false);
         const u32x2 s1 = __builtin_amdgcn_permlane16_swap(even[1], odd[1], false, false);
         const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-        if (last) Epilogue::store(dest, where_last, ch0 + (S::IO - 1) * 16, ch0 + S::IO * 16, jt * 16, v);
-        else Epilogue::store(dest, where_pair[m], ch0 + 32 * m, ch0 + 32 * m + 32, jt * 16, v);
+        if (last) Epilogue::store(dest, where_last, ch0 + (S::IO - 1) * 16, ch0 + S::IO * 16, (S::IO - 1) * 16, jt * 16, v);
+        else Epilogue::store(dest, where_pair[m], ch0 + 32 * m, ch0 + 32 * m + 32, 32 * m, jt * 16, v);
     };
 
     park(lds);
@@ -549,20 +601,31 @@ hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_t
     return hipErrorInvalidValue;
 }
 
+template <class T>
+hipError_t run_qkv_project(const void* x, const void* w_qkv, void* q_ms, long q_ms_stride, void* kv_raw,
+                           long kv_tok_stride, long kv_head_stride, long kv_span, long n_tokens, int c_in, int heads,
+                           hipStream_t stream) {
+    const int c_out = 3 * heads * 16;
+#ifndef MSLA_PROJ_NO_WS
+    if constexpr (sizeof(T) == 2 && MSLA_WS_IO == 3) {
+        // weight-stationary with one head a wave
+        const QkvHeadDest<T> ep{(T*)q_ms, q_ms_stride, (T*)kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, heads * 16};
+        if (c_in <= 128) return run_project_ws<T, 4, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
+        if (c_in <= 256) return run_project_ws<T, 8, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
+    }
+#endif
+    return run_project<T>(x, w_qkv, n_tokens, c_in, c_out,
+                          QkvSplitDest<T>{(T*)q_ms, q_ms_stride, (T*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
+                                          n_tokens, heads * 16}, stream);
+}
+
 hipError_t launch_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
                               void* kv_raw, long kv_tok_stride, long kv_head_stride, long kv_span,
                               long n_tokens, int c_in, int heads, hipStream_t stream) {
-    const int c_out = 3 * heads * 16;
     switch (dt) {
-        case 0: return run_project<float>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<float>{(float*)q_ms, q_ms_stride, (float*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
-                                           n_tokens, heads * 16}, stream);
-        case 1: return run_project<_Float16>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<_Float16>{(_Float16*)q_ms, q_ms_stride, (_Float16*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
-                                           n_tokens, heads * 16}, stream);
-        case 2: return run_project<__bf16>(x, w_qkv, n_tokens, c_in, c_out,
-                    QkvSplitDest<__bf16>{(__bf16*)q_ms, q_ms_stride, (__bf16*)kv_raw, kv_tok_stride, kv_head_stride, kv_span,
-                                           n_tokens, heads * 16}, stream);
+        case 0: return run_qkv_project<float>(x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, c_in, heads, stream);
+        case 1: return run_qkv_project<_Float16>(x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, c_in, heads, stream);
+        case 2: return run_qkv_project<__bf16>(x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, c_in, heads, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -288,6 +288,30 @@ def test_forward_writes_only_its_own_rows(dtype, B, C, H, W, heads, scales):
 
 
 @pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
+    ("f16", 1, 272, 17, 40, 17, (5,)),      # tiled projection: its 128-token tiles overhang the head-major K|V map's padding
+    ("f16", 3, 256, 64, 96, 16, (5,)),      # weight-stationary kernels, several tiles per workgroup
+    ("bf16", 2, 128, 33, 35, 8, (3, 5)),
+])
+def test_forward_repeated_launches_agree(dtype, B, C, H, W, heads, scales):
+    """The whole module launched many times on the same input gives the same bits every time: a
+    write that lands where another workgroup also writes (a row past the last token, a piece of a
+    neighbouring head) shows up as a difference between launches sooner or later."""
+    d = 16
+    print(f"forward, 60 launches: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
+    t = wk.random_module(31 + C + H, dtype, B, C, H, W, heads, d, scales)
+    x = dev(t["x"], dtype)
+    wdw, wg = weights(t, dtype, scales)
+    wq, wp = dev(t["w_qkv"], dtype), dev(t["w_proj"], dtype)
+    ws = poisoned_workspace(B, C, H, W, heads, d, scales, dtype)
+    first = msla.msla_forward(x, wq, wdw, wg, wp, heads, d, scales, 1e-15, workspace=ws).clone()
+    differing = 0
+    for _ in range(60):
+        out = msla.msla_forward(x, wq, wdw, wg, wp, heads, d, scales, 1e-15, workspace=ws)
+        differing += int(not torch.equal(first, out))
+    assert differing == 0, f"{differing} of 60 launches differ from the first"
+
+
+@pytest.mark.parametrize("dtype,B,C,H,W,heads,scales", [
     ("f16", 2, 64, 37, 70, 4, (3, 5)),
     ("bf16", 1, 128, 64, 64, 8, (5,)),
 ])
