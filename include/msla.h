@@ -17,9 +17,12 @@
  *     in the storage dtype `dt`; every sum is accumulated in fp32.  `scales`
  *     is a HOST pointer.  `stream` is a hipStream_t passed as void*.
  *   - The caller owns every buffer, including `workspace` (size it with
- *     msla_workspace_bytes).  The library allocates and frees nothing, keeps
- *     no state between calls and is re-entrant as long as concurrent calls
- *     use different workspaces and outputs.
+ *     msla_workspace_bytes).  The library allocates and frees nothing and is
+ *     re-entrant as long as concurrent calls use different workspaces and
+ *     outputs.  The only state it keeps between calls are per-process caches
+ *     of device properties (the compute-unit count of the first device used;
+ *     per kernel and device, that its LDS limit has been raised), which do not
+ *     depend on any call's arguments.
  *   - Work is enqueued on `stream`; the call returns without synchronising.
  *     Buffers must stay alive and unmodified until the stream has passed it.
  *     Outputs must not alias inputs or the workspace.
@@ -89,6 +92,32 @@ msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw,
                          int B, int C, int H, int W, int heads, int head_dim,
                          const int* scales, int n_scales,
                          float eps, msla_dtype dt, msla_layout layout, void* stream);
+
+/* msla_forward with a choice of code path (same computation and result contract, Section 3.1).
+ * options: bitwise OR of
+ *   MSLA_OPT_GENERAL_AGGREGATION  the 16-bit storage types take the general (vector-ALU
+ *       depthwise) aggregation kernel instead of the matrix-core one.  msla_forward itself
+ *       takes it only for an image whose maps span 2 GiB or more; this is how that path
+ *       is reached at ordinary sizes.
+ *   MSLA_OPT_STAGE_PROJECT / _AGGREGATE / _FINALIZE / _APPLY  (for profiling) when any of these
+ *       is set, only the kernels of the named stages are enqueued: the Q/K/V projection; the
+ *       aggregation + partial Eq. (3) states; the fixed-order sum of the partial states; the
+ *       fused normalise-and-apply + output projection.  A stage reads what the stages before it
+ *       left in `workspace`, so a complete call with the same arguments must have run on that
+ *       workspace before; MSLA_NHWC only (else MSLA_ERR_UNSUPPORTED).
+ * Any other bit returns MSLA_ERR_INVALID_ARG. */
+#define MSLA_OPT_GENERAL_AGGREGATION 1u
+#define MSLA_OPT_STAGE_PROJECT 2u
+#define MSLA_OPT_STAGE_AGGREGATE 4u
+#define MSLA_OPT_STAGE_FINALIZE 8u
+#define MSLA_OPT_STAGE_APPLY 16u
+msla_status msla_forward_opts(const void* x, const void* w_qkv, const void* w_dw,
+                              const void* w_gpw, const void* w_proj, void* out,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int C, int H, int W, int heads, int head_dim,
+                              const int* scales, int n_scales,
+                              float eps, msla_dtype dt, msla_layout layout, void* stream,
+                              unsigned options);
 
 /* msla_forward with stage timing (for benchmarks; same computation, Section 3.1).
  * events: HOST array of 5 hipEvent_t created by the caller with timing enabled.  They are

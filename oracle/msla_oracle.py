@@ -201,25 +201,13 @@ def forward(x, w_qkv, w_dw, w_gpw, w_proj, heads: int, d: int, scales, eps: floa
 
 
 # ----------------------------------------------------------------------------
-# The same module composed stage by stage (Fig. 2 right), with two hooks that
-# the parity tests need and the one-call C entry points above do not have:
-#
-#   store   callable(ndarray) -> ndarray or None.  Reading "16-bit storage,
-#           fp32 sums": a token map that a two-pass evaluation of Eq. (3) has
-#           to keep between its passes is STORED, i.e. rounded once to the
-#           storage type: the projected Q/K/V tokens, and the aggregated Q
-#           tokens of every branch (aggregated K and V only feed the sums of
-#           Eq. (3) and need not be kept).  `store` is that rounding (the
-#           caller passes the input generator's rounding; this file does no
-#           rounding of its own).  None = nothing is rounded (plain fp64).
-#   q_tokens  optional [B,H,W,S*heads*d] array that replaces the Q tokens of
-#           every branch in Eq. (3).  Eq. (3) is 0/0 where a token's rectified
-#           query vanishes and discontinuous next to it: which components of Q
-#           pass the ReLU is a discrete decision taken by floating point, so a
-#           comparison has to take it on the same stored values on both sides.
+# The same module composed stage by stage (Fig. 2 right) from the stage
+# functions above, with every intermediate returned.  Nothing is rounded and
+# nothing is taken from outside: this is the paper's definition, only split at
+# the arrows of the figure (a test pins it to the one-call forms).
 # ----------------------------------------------------------------------------
 
-def branch_maps(qkv, w_dw, w_gpw, heads: int, d: int, scales, store=None):
+def branch_maps(qkv, w_dw, w_gpw, heads: int, d: int, scales):
     """[raw map, aggregated map per scale], each [B,H,W,3*heads*d]; every
     aggregated branch reads the raw map (Section 3.1, last paragraph)."""
     qkv = _f64(qkv)
@@ -230,12 +218,7 @@ def branch_maps(qkv, w_dw, w_gpw, heads: int, d: int, scales, store=None):
     for a, k in enumerate(scales):
         w = w_dw[off:off + ch * k * k].reshape(ch, k, k)
         off += ch * k * k
-        agg = grouped_pw(dwconv(qkv, w), _f64(w_gpw)[a])
-        if store is not None:
-            B, H, W, _ = agg.shape
-            v = agg.reshape(B, H, W, heads, 3, d)
-            v[..., 0, :] = _f64(store(np.ascontiguousarray(v[..., 0, :])))
-        maps.append(agg)
+        maps.append(grouped_pw(dwconv(qkv, w), _f64(w_gpw)[a]))
     return maps
 
 
@@ -246,7 +229,7 @@ def q_tokens_of(maps, heads: int, d: int) -> np.ndarray:
                            for m in maps], axis=-1)
 
 
-def attention_of_maps(maps, heads: int, d: int, eps: float, q_tokens=None):
+def attention_of_maps(maps, heads: int, d: int, eps: float):
     """Eq. (3) per image / branch / head on the given branch maps.
     Returns (att [B,H,W,S*heads*d], kv [B,S,heads,d,d+1])."""
     B, H, W, ch = maps[0].shape
@@ -257,10 +240,6 @@ def attention_of_maps(maps, heads: int, d: int, eps: float, q_tokens=None):
     kv = np.empty((B, S, heads, d, d + 1), dtype=np.float64)
     for s, m in enumerate(maps):
         m = _f64(m).reshape(B, N, ch)
-        if q_tokens is not None:
-            m = m.copy().reshape(B, N, heads, 3, d)
-            m[:, :, :, 0, :] = _f64(q_tokens).reshape(B, N, S, heads, d)[:, :, s]
-            m = m.reshape(B, N, ch)
         for b in range(B):
             tok = np.ascontiguousarray(m[b])
             kv[b, s] = kv_state(tok, heads, d)
@@ -268,31 +247,12 @@ def attention_of_maps(maps, heads: int, d: int, eps: float, q_tokens=None):
     return att.reshape(B, H, W, S * Ct), kv
 
 
-def gate_margin(q_tokens, kv, heads: int, d: int) -> np.ndarray:
-    """Conditioning of Eq. (3) per (token, head-branch):
-    (relu(Q).Ksum) / (|Q|.Ksum) in [0, 1]; small values mean the denominator is
-    a small remainder of cancelled rounding errors of Q.  [B,H,W,S*heads]."""
-    q = _f64(q_tokens)
-    B, H, W, _ = q.shape
-    S = kv.shape[1]
-    q = q.reshape(B, H * W, S, heads, d)
-    ks = _f64(kv)[..., d]                                  # [B,S,heads,d]
-    num = np.einsum("bnshe,bshe->bnsh", np.maximum(q, 0.0), ks)
-    den = np.einsum("bnshe,bshe->bnsh", np.abs(q), ks)
-    out = np.where(den > 0, num / np.where(den > 0, den, 1.0), 1.0)
-    return out.reshape(B, H, W, S * heads)
-
-
-def forward_staged(x, w_qkv, w_dw, w_gpw, w_proj, heads: int, d: int, scales, eps: float,
-                   store=None, q_tokens=None, return_parts: bool = False):
-    """Whole module, stage by stage.  With store=None and q_tokens=None this is
-    exactly `forward` (pinned by a test)."""
+def forward_staged(x, w_qkv, w_dw, w_gpw, w_proj, heads: int, d: int, scales, eps: float):
+    """Whole module, stage by stage: (out, parts) with parts = the projected
+    map, the branch maps, the attention rows, the Eq. (3) states and the Q
+    tokens of every branch.  `out` is exactly `forward` (pinned by a test)."""
     qkv = linear(x, w_qkv)
-    if store is not None:
-        qkv = _f64(store(qkv))
-    maps = branch_maps(qkv, w_dw, w_gpw, heads, d, scales, store)
-    att, kv = attention_of_maps(maps, heads, d, eps, q_tokens)
+    maps = branch_maps(qkv, w_dw, w_gpw, heads, d, scales)
+    att, kv = attention_of_maps(maps, heads, d, eps)
     out = linear(att, w_proj)
-    if return_parts:
-        return out, {"qkv": qkv, "maps": maps, "att": att, "kv": kv, "q_tokens": q_tokens_of(maps, heads, d)}
-    return out
+    return out, {"qkv": qkv, "maps": maps, "att": att, "kv": kv, "q_tokens": q_tokens_of(maps, heads, d)}

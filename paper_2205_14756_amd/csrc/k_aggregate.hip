@@ -189,8 +189,11 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a)
                 f32x4 a4 = {acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
                 if (!valid[r]) a4 = z;       // tokens outside the image contribute nothing
                 // depthwise sums as MFMA operand(s)
+                // (Q's sums always as hi + lo: the sign of an aggregated Q component decides what
+                // passes the rectifier of Eq. (2), so it keeps its fp32 accuracy up to its store)
                 Frag dwf, dwf_lo;
-                if constexpr (Tr::kHiLo) frag_split<T>(a4, dwf, dwf_lo);
+                constexpr bool kWide = sizeof(T) == 2;     // fp32 operands are exact already
+                if (Tr::kHiLo || (kWide && t == 0)) frag_split<T>(a4, dwf, dwf_lo);
                 else dwf = frag_from_f32<T>(a4);
                 const Frag rawf = valid[r] ? center[r] : frag_zero<T>();
                 if (t == 1) {
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a)
                 } else {
                     // transposed: lane (strip i, q) <- output channels 4q..4q+3 of its own token r
                     f32x4 qq = Tr::mma16(z, gpw[0], dwf);
-                    if constexpr (Tr::kHiLo) qq = Tr::mma16(qq, gpw[0], dwf_lo);
+                    if constexpr (Tr::kHiLo || kWide) qq = Tr::mma16(qq, gpw[0], dwf_lo);
                     if (valid[r]) {
                         T* dst = q_ms + (tok0 + r) * q_ms_ts + h * 16 + q * 4;
                         store_frag<T>(dst + (long)a.branch * Ct, frag_from_f32<T>(qq));

@@ -470,8 +470,14 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 }
                 return;
             }
+            // The depthwise sums of Q always go to the grouped 1x1 as hi + lo pairs, whatever the
+            // storage type: which components of the aggregated Q pass the rectifier of Eq. (2) is a
+            // discrete decision, so that Q must carry the accuracy of its fp32 sums up to the one
+            // rounding of its store (a sum rounded to 11 bits first moves a component that is small
+            // against its 16 terms across zero).  K only feeds the sums of Eq. (3), which are
+            // continuous in it: fp16 takes its depthwise sums rounded once.
             Frag dwf, dwf_lo;
-            if constexpr (Tr::kHiLo) frag_split<T>(tq, dwf, dwf_lo);
+            if (Tr::kHiLo || t == 0) frag_split<T>(tq, dwf, dwf_lo);
             else dwf = frag_from_f32<T>(tq);
             if (t == 1) {
                 f32x4 kf = Tr::mma16(z, dwf, gpw_k);
@@ -479,7 +485,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
                 s2v[it & 1] = kf;
             } else {
                 f32x4 qq = Tr::mma16(z, gpw_q, dwf);
-                if constexpr (Tr::kHiLo) qq = Tr::mma16(qq, gpw_q, dwf_lo);
+                qq = Tr::mma16(qq, gpw_q, dwf_lo);
                 s2v[it & 1] = qq;
             }
         };

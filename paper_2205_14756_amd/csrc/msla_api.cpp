@@ -1,17 +1,22 @@
 // Host side of the C ABI declared in include/msla.h: argument validation,
-// workspace carving and the launch sequence.  No allocation, no global state,
-// no synchronisation; every failure before the first launch leaves the stream
-// untouched.
+// workspace carving and the launch sequence.  No allocation, no synchronisation,
+// no state that depends on a call's arguments (the only statics are per-process
+// caches of device properties: the compute-unit count and "this kernel's LDS
+// limit has been raised on this device"); every failure before the first
+// launch leaves the stream untouched.
 #include "../../include/msla.h"
 
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "msla_kernels.h"
 
 namespace {
 
 constexpr int kMaxScales = 7;
+constexpr unsigned kStageBits = MSLA_OPT_STAGE_PROJECT | MSLA_OPT_STAGE_AGGREGATE | MSLA_OPT_STAGE_FINALIZE |
+                                MSLA_OPT_STAGE_APPLY;
+// with no stage bit set every stage runs
+bool stage_wanted(unsigned options, unsigned bit) { return (options & kStageBits) == 0 || (options & bit) != 0; }
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -110,7 +115,7 @@ size_t dw_weight_elems(const Shape& s, int upto) {
 msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, int q_hs, const void* k,
                       long k_ts, int k_hs, const void* v, long v_ts, int v_hs, const void* w_dw,
                       const void* w_gpw, char* ws, const Workspace& wo, void* q_ms, int copy_raw_q,
-                      hipStream_t stream, void* event_before_finalize = nullptr) {
+                      hipStream_t stream, unsigned options = 0, void* event_before_finalize = nullptr) {
     const size_t e = elem_size(dt);
     msla::AggregateArgs a;
     a.q = q; a.k = k; a.v = v;
@@ -120,21 +125,21 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
     a.partials = reinterpret_cast<float*>(ws + wo.partials);
     a.B = s.B; a.H = s.H; a.W = s.W; a.heads = s.heads; a.S = s.S;
     a.nchunks = s.nchunks; a.tiles_per_chunk = s.tiles_per_chunk;
-    if (s.n_scales == 0) {
+    const bool aggregate = stage_wanted(options, MSLA_OPT_STAGE_AGGREGATE);
+    if (s.n_scales == 0 && aggregate) {
         a.w_dw = nullptr; a.w_gpw = nullptr; a.ks = 0; a.branch = 0; a.do_raw = 1; a.copy_raw_q = copy_raw_q;
         if (msla::launch_raw_state((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
     }
-    for (int i = 0; i < s.n_scales; ++i) {
+    for (int i = 0; i < s.n_scales && aggregate; ++i) {
         a.w_dw = static_cast<const char*>(w_dw) + dw_weight_elems(s, i) * e;
         a.w_gpw = static_cast<const char*>(w_gpw) + (size_t)i * 3 * s.Ct * 16 * e;
         a.ks = s.scales[i];
         a.branch = i + 1;
         a.do_raw = (i == 0);
         a.copy_raw_q = (i == 0) ? copy_raw_q : 0;
-        // (MSLA_AGG_GENERAL=1 in the environment sends every case to the general kernel: that is how
-        // the tests reach the path below without a 2 GiB image)
-        const char* force = getenv("MSLA_AGG_GENERAL");
-        const bool general = dt == MSLA_F32 || (force && force[0] == '1');
+        // (MSLA_OPT_GENERAL_AGGREGATION sends every case to the general kernel: that is how the tests
+        // reach the path below without a 2 GiB image)
+        const bool general = dt == MSLA_F32 || (options & MSLA_OPT_GENERAL_AGGREGATION);
         hipError_t e_launch = (dt == MSLA_F32) ? msla::launch_aggregate((int)dt, a, stream)
                               : general        ? hipErrorNotSupported
                                                : msla::launch_aggregate_mfma((int)dt, a, stream);
@@ -153,7 +158,8 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
         hipEventRecord(static_cast<hipEvent_t>(event_before_finalize), stream) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     const int n_states = s.B * s.S * s.heads;
-    if (msla::launch_state_finalize((int)dt, a.partials, reinterpret_cast<float*>(ws + wo.kv32), ws + wo.kvfrag,
+    if (stage_wanted(options, MSLA_OPT_STAGE_FINALIZE) &&
+        msla::launch_state_finalize((int)dt, a.partials, reinterpret_cast<float*>(ws + wo.kv32), ws + wo.kvfrag,
                                     reinterpret_cast<float*>(ws + wo.kvscale), n_states, s.nchunks,
                                     stream) != hipSuccess)
         return MSLA_ERR_LAUNCH;
@@ -204,8 +210,10 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
                                 const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B,
                                 int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
                                 float eps, msla_dtype dt, msla_layout layout, void* stream,
-                                void* const* events) {
+                                void* const* events, unsigned options) {
     if (!x || !w_qkv || !w_proj || !out || !workspace || C <= 0) return MSLA_ERR_INVALID_ARG;
+    if (options & ~(MSLA_OPT_GENERAL_AGGREGATION | kStageBits)) return MSLA_ERR_INVALID_ARG;
+    if ((options & kStageBits) && layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
     if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
     if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
     if (layout != MSLA_NHWC && layout != MSLA_NCHW) return MSLA_ERR_INVALID_ARG;
@@ -247,17 +255,19 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     const long kv_ts = hm ? 32 : 2L * s.Ct;                       // elements from token to token
     const long kv_hs = hm ? kv_padded_tokens(s) * 32 : 32;        // ... from head to head
     const long kv_span = hm ? kv_padded_tokens(s) * 2 * s.Ct : s.T * 2 * s.Ct;
-    if (msla::launch_qkv_project((int)dt, x_tok, w_qkv, q_ms, q_ms_ts, kv_raw, kv_ts, kv_hs, kv_span, s.T, C, s.heads,
+    if (stage_wanted(options, MSLA_OPT_STAGE_PROJECT) &&
+        msla::launch_qkv_project((int)dt, x_tok, w_qkv, q_ms, q_ms_ts, kv_raw, kv_ts, kv_hs, kv_span, s.T, C, s.heads,
                                  hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (!mark(1)) return MSLA_ERR_LAUNCH;
     // aggregation + Eq. (3) state
     st = run_state(s, dt, q_ms, q_ms_ts, 16, kv_raw, kv_ts, (int)kv_hs, kv_raw + 16 * e, kv_ts, (int)kv_hs, w_dw, w_gpw,
-                   ws, wo, q_ms, /*copy_raw_q=*/0, hs, events ? events[2] : nullptr);
+                   ws, wo, q_ms, /*copy_raw_q=*/0, hs, options, events ? events[2] : nullptr);
     if (st != MSLA_OK) return st;
     if (!mark(3)) return MSLA_ERR_LAUNCH;
     // normalise-and-apply fused with the output projection
-    if (msla::launch_apply_project((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale),
+    if (stage_wanted(options, MSLA_OPT_STAGE_APPLY) &&
+        msla::launch_apply_project((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale),
                                    w_proj, out_tok, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (layout == MSLA_NCHW &&
@@ -272,7 +282,15 @@ msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw, con
                          int H, int W, int heads, int head_dim, const int* scales, int n_scales, float eps,
                          msla_dtype dt, msla_layout layout, void* stream) {
     return forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads,
-                        head_dim, scales, n_scales, eps, dt, layout, stream, nullptr);
+                        head_dim, scales, n_scales, eps, dt, layout, stream, nullptr, 0u);
+}
+
+msla_status msla_forward_opts(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                              const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B, int C,
+                              int H, int W, int heads, int head_dim, const int* scales, int n_scales, float eps,
+                              msla_dtype dt, msla_layout layout, void* stream, unsigned options) {
+    return forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads,
+                        head_dim, scales, n_scales, eps, dt, layout, stream, nullptr, options);
 }
 
 msla_status msla_forward_profiled(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
@@ -284,7 +302,7 @@ msla_status msla_forward_profiled(const void* x, const void* w_qkv, const void* 
     for (int i = 0; i < 5; ++i)
         if (events[i] == nullptr) return MSLA_ERR_INVALID_ARG;
     return forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads,
-                        head_dim, scales, n_scales, eps, dt, layout, stream, events);
+                        head_dim, scales, n_scales, eps, dt, layout, stream, events, 0u);
 }
 
 msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms_out,

@@ -26,7 +26,10 @@ MSLA_ERR_LAUNCH = -4
 MSLA_F32, MSLA_F16, MSLA_BF16 = 0, 1, 2
 MSLA_NHWC, MSLA_NCHW = 0, 1
 
-EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_profiled",
+MSLA_OPT_GENERAL_AGGREGATION = 1
+MSLA_OPT_STAGE_PROJECT, MSLA_OPT_STAGE_AGGREGATE, MSLA_OPT_STAGE_FINALIZE, MSLA_OPT_STAGE_APPLY = 2, 4, 8, 16
+
+EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
            "msla_core_forward",
            "msla_multiscale_state", "msla_linear")
 
@@ -57,6 +60,8 @@ def load_library() -> ctypes.CDLL:
     lib.msla_workspace_bytes.restype = i
     lib.msla_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, ip, i, f, i, i, vp]
     lib.msla_forward.restype = i
+    lib.msla_forward_opts.argtypes = lib.msla_forward.argtypes + [ctypes.c_uint]
+    lib.msla_forward_opts.restype = i
     lib.msla_forward_profiled.argtypes = lib.msla_forward.argtypes + [ctypes.POINTER(vp)]
     lib.msla_forward_profiled.restype = i
     lib.msla_core_forward.argtypes = [vp, vp, vp, vp, vp, sz, i, i, i, i, i, ip, i, f, i, vp]
@@ -112,9 +117,9 @@ def new_workspace(B, C, H, W, heads, head_dim, scales, dtype, device="cuda") -> 
 
 
 def msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps=1e-15, out=None,
-                 workspace=None, stream=None, layout=MSLA_NHWC):
+                 workspace=None, stream=None, layout=MSLA_NHWC, options=0):
     """out = MSLA(x): x [B,H,W,C] -> out [B,H,W,C], or [B,C,H,W] both with layout=MSLA_NCHW
-    (see include/msla.h for every shape)."""
+    (see include/msla.h for every shape).  options != 0 goes through msla_forward_opts."""
     _dev(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace)
     if layout == MSLA_NCHW:
         B, C, H, W = x.shape
@@ -125,12 +130,23 @@ def msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps=1e-
     if workspace is None:
         workspace = new_workspace(B, C, H, W, heads, head_dim, scales, x.dtype, x.device)
     sc, ns = _scales(scales)
-    st = load_library().msla_forward(_ptr(x), _ptr(w_qkv), _ptr(w_dw), _ptr(w_gpw), _ptr(w_proj), _ptr(out),
-                                     _ptr(workspace), workspace.numel(), B, C, H, W, heads, head_dim, sc, ns,
-                                     float(eps), _DTYPES[x.dtype], layout, _stream(stream))
+    args = (_ptr(x), _ptr(w_qkv), _ptr(w_dw), _ptr(w_gpw), _ptr(w_proj), _ptr(out), _ptr(workspace),
+            workspace.numel(), B, C, H, W, heads, head_dim, sc, ns, float(eps), _DTYPES[x.dtype], layout,
+            _stream(stream))
+    if options:
+        st = load_library().msla_forward_opts(*args, int(options))
+    else:
+        st = load_library().msla_forward(*args)
     if st != MSLA_OK:
         raise MslaError(st, "msla_forward")
     return out
+
+
+def msla_forward_opts(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps, options, out=None,
+                      workspace=None, stream=None, layout=MSLA_NHWC):
+    """msla_forward with a choice of code path / stages (MSLA_OPT_* bits, see include/msla.h)."""
+    return msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps, out=out,
+                        workspace=workspace, stream=stream, layout=layout, options=options)
 
 
 def msla_forward_profiled(x, w_qkv, w_dw, w_gpw, w_proj, heads, head_dim, scales, eps, out, workspace,

@@ -30,7 +30,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == {"msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_profiled",
+    assert set(names) == {"msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
                           "msla_core_forward",
                           "msla_multiscale_state", "msla_linear"}
     for n in names:
@@ -147,3 +147,16 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in (r.stderr + r.stdout)
     assert not any(line.startswith("{") for line in r.stdout.splitlines())
+
+
+def test_forward_opts_rejects_unknown_bits_and_stage_bits_with_nchw(lib):
+    sc = (ctypes.c_int * 1)(5)
+    vp = ctypes.c_void_p
+    lib.msla_forward_opts.argtypes = [vp] * 7 + [ctypes.c_size_t] + [ctypes.c_int] * 6 + [ctypes.POINTER(ctypes.c_int), ctypes.c_int,
+                                                                                          ctypes.c_float, ctypes.c_int, ctypes.c_int, vp, ctypes.c_uint]
+    lib.msla_forward_opts.restype = ctypes.c_int
+    p = vp(0x1000)      # never dereferenced: every check below fails on the host
+    call = lambda layout, opts: lib.msla_forward_opts(p, p, p, p, p, p, p, 1 << 40, 1, 64, 8, 8, 4, 16, sc, 1, 1e-15, F16,
+                                                      layout, None, opts)
+    assert call(0, 32) == INVALID and call(0, 0x80000000) == INVALID
+    assert call(1, 2) == UNSUPPORTED and call(1, 16 | 1) == UNSUPPORTED

@@ -4,41 +4,29 @@ element by element on the same seeded inputs.
 Bar (max over all elements): |gpu - oracle| <= tol * max|oracle| with
 tol = 1e-4 for fp32 storage and 5e-3 for fp16 / bf16 storage (fp32 sums).
 
-Protocol for anything downstream of the ReLU gate of Eq. (3).  Eq. (3) is 0/0
-where a token's rectified query vanishes, and next to that point the result
-swings by O(1) with the sign of one tiny Q component: which components pass the
-ReLU is a discrete decision taken by floating point.  So
-  (G) the gate is taken on the same stored values on both sides: the oracle
-      evaluates Eq. (3) with the Q tokens the GPU path stored (its stage entry
-      points return them), everything else being the oracle's own; those stored
-      tokens and the Eq. (3) states are themselves compared with the oracle's
-      (they are continuous in the inputs);
-  (S) reading "16-bit storage, fp32 sums": the token maps a two-pass evaluation
-      has to keep between its passes (projected Q/K/V, aggregated Q) are rounded
-      once to the storage type in the oracle too (`store`); a stored map of the
-      GPU is compared with the oracle's value BEFORE that rounding, since two
-      independent roundings of nearly equal numbers can differ by a whole ulp;
-  (P) in addition the plain fp64 oracle, with no rounding anywhere, is compared
-      on every token whose gate is well conditioned (gate_margin >= 64 u, u the
-      storage type's unit roundoff).
+The expected value is always the PLAIN oracle (``oracle/``: the paper's definition in fp64, no
+rounding, nothing taken from the GPU), on every token.  The only tokens judged differently are an
+explicit, printed, counted list of tokens where Eq. (3) itself is ill-posed under 16-bit storage of Q
+(the rectified part of a Q row is a rounding-sized remainder); each of them must be predicted by the
+plain oracle's gate margin and be an admissible value of Eq. (3), and their number must not exceed
+what storage rounding alone does on the CPU -- see tests/parity_model.py, which holds that protocol
+and whose own CPU tests (tests/test_parity_model.py) derive its threshold.
+Continuous intermediates (the projected map, the multi-scale Q tokens, the Eq. (3) states) are
+compared with the plain oracle's as well.
 """
 import numpy as np
 import pytest
 import torch
 
+import parity_model as pm
 from oracle import msla_oracle as orc
 from paper_2205_14756_amd import msla
 from paper_2205_14756_amd import workloads as wk
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "f16": 5e-3, "bf16": 5e-3}
+TOL = pm.TOL
 TDT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
-GATE_THETA = {"f32": 64 * 2.0 ** -24, "f16": 64 * 2.0 ** -11, "bf16": 64 * 2.0 ** -8}
-# (P) for bf16: rounding the token maps to 8 significant bits is part of the bf16 reading and by
-# itself moves the plain-fp64 result by up to ~4e-3 of max|out|, on top of the up to 3.9e-3 of the
-# output rounding, so the no-rounding comparison is held to twice the stated bar there.
-TOL_PLAIN = {"f32": 1e-4, "f16": 5e-3, "bf16": 1e-2}
 
 
 def dev(a, dtype):
@@ -66,13 +54,13 @@ def weights(t, dtype, scales):
     return (dev(t["w_dw"], dtype) if len(scales) else None, dev(t["w_gpw"], dtype) if len(scales) else None)
 
 
-def run_forward(t, dtype, heads, d, scales, eps=1e-15):
+def run_forward(t, dtype, heads, d, scales, eps=1e-15, options=0):
     x = dev(t["x"], dtype)
     B, H, W, C = x.shape
     wdw, wg = weights(t, dtype, scales)
     out = torch.full_like(x, float("nan"))
     msla.msla_forward(x, dev(t["w_qkv"], dtype), wdw, wg, dev(t["w_proj"], dtype), heads, d, scales, eps,
-                      out=out, workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype))
+                      out=out, workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype), options=options)
     return host(out)
 
 
@@ -100,28 +88,22 @@ def check_states(kv, kv_ref, tol):
     return worst
 
 
-def check_module(t, dtype, heads, d, scales, eps=1e-15):
+def check_module(t, dtype, heads, d, scales, eps=1e-15, options=0, stages=True):
+    """msla_forward against the plain oracle on every token (pm.judge_module), and -- through the
+    stage entry points -- the continuous intermediates against the plain oracle's."""
     tol = TOL[dtype]
-    store = lambda a: wk.round_to_dtype(a, dtype)
-    args = (t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d, scales, eps)
-    got = run_forward(t, dtype, heads, d, scales, eps)
-    qkv_g, q_g, kv_g = gpu_stage_chain(t, dtype, heads, d, scales)
-    _, parts = orc.forward_staged(*args, store=store, return_parts=True)
-    e_qkv = rel_err(qkv_g, orc.linear(t["x"], t["w_qkv"]))
-    unrounded = orc.branch_maps(parts["qkv"], t["w_dw"], t["w_gpw"], heads, d, scales)
-    e_q = rel_err(q_g, orc.q_tokens_of(unrounded, heads, d))
-    e_kv = check_states(kv_g, parts["kv"], tol)
-    ref_gate = orc.forward_staged(*args, store=store, q_tokens=q_g)          # (G) + (S)
-    e_out = rel_err(got, ref_gate)
-    plain = orc.forward(*args)                                               # (P)
-    margin = orc.gate_margin(parts["q_tokens"], parts["kv"], heads, d).min(-1)
-    well = margin >= GATE_THETA[dtype]
-    e_plain = float(np.abs(got - plain)[well].max() / np.abs(plain).max()) if well.any() else 0.0
-    print(f"  qkv {e_qkv:.2e}  q_ms {e_q:.2e}  kv {e_kv:.2e}  out(gate-consistent) {e_out:.2e}  "
-          f"out(plain fp64, {well.mean() * 100:.2f}% of tokens) {e_plain:.2e}  tol {tol:.0e}", flush=True)
-    assert e_qkv <= tol and e_q <= tol
-    assert e_out <= tol
-    assert e_plain <= TOL_PLAIN[dtype]
+    got = run_forward(t, dtype, heads, d, scales, eps, options)
+    j = pm.judge_module(got, t, dtype, heads, d, scales, eps)
+    print(f"  {j}", flush=True)
+    if stages:
+        _, parts = orc.forward_staged(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d, scales, eps)
+        qkv_g, q_g, kv_g = gpu_stage_chain(t, dtype, heads, d, scales)
+        e_qkv = rel_err(qkv_g, parts["qkv"])
+        e_q = rel_err(q_g, parts["q_tokens"])
+        e_kv = check_states(kv_g, parts["kv"], tol)
+        print(f"  stages vs plain oracle: qkv {e_qkv:.2e}  q_ms {e_q:.2e}  kv {e_kv:.2e}  (bar {tol:.0e})", flush=True)
+        assert e_qkv <= tol and e_q <= tol
+    return j
 
 
 # ----------------------------------------------------------------- S0 / S5 stage
@@ -197,29 +179,22 @@ def test_multiscale_state_and_core(dtype, B, H, W, heads, scales):
     tol = TOL[dtype]
     print(f"state+core {dtype} B={B} {H}x{W} heads={heads} scales={scales}", flush=True)
     t = wk.random_module(B * 1000 + H * 10 + W, dtype, B, C, H, W, heads, d, scales)
-    store = lambda a: wk.round_to_dtype(a, dtype)
-    qkv = store(orc.linear(t["x"], t["w_qkv"]))
-    maps = orc.branch_maps(qkv, t["w_dw"], t["w_gpw"], heads, d, scales, store)
-    att_ref, kv_ref = orc.attention_of_maps(maps, heads, d, 1e-15)
+    qkv = wk.round_to_dtype(orc.linear(t["x"], t["w_qkv"]), dtype)         # the given projected map
+    maps = orc.branch_maps(qkv, t["w_dw"], t["w_gpw"], heads, d, scales)
+    _, kv_ref = orc.attention_of_maps(maps, heads, d, 1e-15)
     q_ref = orc.q_tokens_of(maps, heads, d)
     wdw, wg = weights(t, dtype, scales)
 
     q_ms, kv = msla.msla_multiscale_state(dev(qkv, dtype), wdw, wg, heads, d, scales,
                                           workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype))
     q_ms, kv = host(q_ms), host(kv)
-    unrounded = orc.branch_maps(qkv, t["w_dw"], t["w_gpw"], heads, d, scales)
-    assert rel_err(q_ms, orc.q_tokens_of(unrounded, heads, d)) <= tol
+    assert rel_err(q_ms, q_ref) <= tol
     assert np.array_equal(q_ms[..., :C], q_ref[..., :C])          # the raw branch is a copy
     check_states(kv, kv_ref, tol)
 
     att = host(msla.msla_core_forward(dev(qkv, dtype), wdw, wg, heads, d, scales, 1e-15,
                                       workspace=poisoned_workspace(B, C, H, W, heads, d, scales, dtype)))
-    att_gate, _ = orc.attention_of_maps(maps, heads, d, 1e-15, q_tokens=q_ms)            # (G)
-    assert rel_err(att, att_gate) <= tol
-    plain = orc.core_forward(qkv, t["w_dw"], t["w_gpw"], heads, d, scales, 1e-15)       # (P)
-    well = np.repeat(orc.gate_margin(q_ref, kv_ref, heads, d), d, axis=-1) >= GATE_THETA[dtype]
-    if well.any():
-        assert np.abs(att - plain)[well].max() / np.abs(plain).max() <= TOL_PLAIN[dtype]
+    print(f"  {pm.judge_core(att, qkv, t, dtype, heads, d, scales, 1e-15)}", flush=True)
 
 
 # ------------------------------------------------------------- whole module
@@ -315,14 +290,13 @@ def test_forward_repeated_launches_agree(dtype, B, C, H, W, heads, scales):
     ("f16", 2, 64, 37, 70, 4, (3, 5)),
     ("bf16", 1, 128, 64, 64, 8, (5,)),
 ])
-def test_forward_general_aggregation_kernel_for_16_bit_types(dtype, B, C, H, W, heads, scales, monkeypatch):
+def test_forward_general_aggregation_kernel_for_16_bit_types(dtype, B, C, H, W, heads, scales):
     """An image whose maps span 2 GiB or more leaves the matrix-core aggregation kernel for the
-    general one (half-height tiles, same chunks); MSLA_AGG_GENERAL=1 takes that path at any size."""
+    general one (half-height tiles, same chunks); msla_forward_opts takes that path at any size."""
     d = 16
-    monkeypatch.setenv("MSLA_AGG_GENERAL", "1")
     print(f"forward, general aggregation kernel: {dtype} B={B} C={C} {H}x{W} heads={heads} scales={scales}", flush=True)
     t = wk.random_module(4242 + C + H, dtype, B, C, H, W, heads, d, scales)
-    check_module(t, dtype, heads, d, scales)
+    check_module(t, dtype, heads, d, scales, options=msla.MSLA_OPT_GENERAL_AGGREGATION, stages=False)
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
@@ -415,14 +389,12 @@ def test_large_magnitude_keys_do_not_overflow_fp16_state():
     # sum_n relu(K_n) exceeds the fp16 range here; the state operands are rescaled, the output is not
     dtype, B, C, H, W, heads, d = "f16", 1, 32, 64, 64, 2, 16
     t = wk.random_module(31337, dtype, B, C, H, W, heads, d, (5,))
-    store = lambda a: wk.round_to_dtype(a, dtype)
-    qkv = store(orc.linear(t["x"], t["w_qkv"]) * 60.0)
-    maps = orc.branch_maps(qkv, t["w_dw"], t["w_gpw"], heads, d, (5,), store)
+    qkv = wk.round_to_dtype(orc.linear(t["x"], t["w_qkv"]) * 60.0, dtype)
+    maps = orc.branch_maps(qkv, t["w_dw"], t["w_gpw"], heads, d, (5,))
     _, kv = orc.attention_of_maps(maps, heads, d, 1e-15)
     assert kv[..., d].max() > 65504
     wdw, wg = weights(t, dtype, (5,))
-    q_ms, kv_g = msla.msla_multiscale_state(dev(qkv, dtype), wdw, wg, heads, d, (5,))
+    _, kv_g = msla.msla_multiscale_state(dev(qkv, dtype), wdw, wg, heads, d, (5,))
     check_states(host(kv_g), kv, TOL[dtype])
     att = host(msla.msla_core_forward(dev(qkv, dtype), wdw, wg, heads, d, (5,), 1e-15))
-    att_gate, _ = orc.attention_of_maps(maps, heads, d, 1e-15, q_tokens=host(q_ms))
-    assert rel_err(att, att_gate) <= TOL[dtype]
+    print(f"  {pm.judge_core(att, qkv, t, dtype, heads, d, (5,), 1e-15)}", flush=True)
