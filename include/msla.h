@@ -154,6 +154,27 @@ msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void*
                                   const int* scales, int n_scales,
                                   msla_dtype dt, void* stream);
 
+/* msla_multiscale_state for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * computation, arguments and results as msla_multiscale_state, except that
+ *   - there is no workspace argument: the per-state buffers (partial states of the workgroups, the
+ *     summed states, their operand form) live in a device array inside the library, of
+ *     MSLA_STATIC_SCRATCH_BYTES on every GPU the library is used on, held until the process ends;
+ *   - q_ms must be given (not NULL): the Q tokens of every branch are an output here;
+ *   - a shape whose per-state buffers exceed that array returns MSLA_ERR_WORKSPACE with nothing
+ *     enqueued.  They take B*S*heads*(1088*(chunks+1) + 2052) bytes plus alignment, chunks being
+ *     the number of workgroups one state's reduction is split over (enough to fill the GPU:
+ *     2 at B*heads = 128, 32 at B*heads = 8); 8 MiB covers e.g. 1500 states at 2 chunks.
+ * It calls no allocating routine.  Every call on a GPU uses that GPU's one array, so calls that
+ * overlap on one GPU (different streams, or threads) race: serialise them.  Nothing in the array has
+ * to start at zero and nothing in it survives as a result: each call overwrites what it reads. */
+#define MSLA_STATIC_SCRATCH_BYTES (8u << 20)
+msla_status msla_multiscale_state_static(const void* qkv, const void* w_dw, const void* w_gpw,
+                                         void* q_ms, float* kv,
+                                         int B, int H, int W, int heads, int head_dim,
+                                         const int* scales, int n_scales,
+                                         msla_dtype dt, void* stream);
+
 /* Stage: a 1x1 projection of a token map (Section 3.1: Q = x W_Q etc., and the
  * final projection):  y[n, o] = sum_c x[n, c] * w[o, c],
  *   x [n_tokens, c_in], w [c_out, c_in], y [n_tokens, c_out]; c_in, c_out multiples of 16. */

@@ -89,14 +89,16 @@ bool kv_head_major(const Shape& s, msla_dtype dt) {
     return dt != MSLA_F32 && s.n_scales > 0 && (size_t)kv_padded_tokens(s) * 2 * s.Ct * elem_size(dt) < (1ull << 31);
 }
 
-Workspace carve(const Shape& s, msla_dtype dt) {
+// with_maps = false: only the small per-state buffers (for an entry point whose caller supplies the
+// token maps itself)
+Workspace carve(const Shape& s, msla_dtype dt, bool with_maps = true) {
     const size_t e = elem_size(dt);
     const size_t n_states = (size_t)s.B * s.S * s.heads;
     Workspace w;
     size_t off = 0;
-    w.q_ms = off;     off += align_up((size_t)s.T * s.S * s.Ct * e);
+    w.q_ms = off;     off += with_maps ? align_up((size_t)s.T * s.S * s.Ct * e) : 0;
     // (token count rounded up to whole projection tiles: the head-major form of this map pads each head)
-    w.kv_raw = off;   off += align_up((size_t)kv_padded_tokens(s) * 2 * s.Ct * e);
+    w.kv_raw = off;   off += with_maps ? align_up((size_t)kv_padded_tokens(s) * 2 * s.Ct * e) : 0;
     w.partials = off; off += align_up(n_states * s.nchunks * 272 * sizeof(float));
     w.kv32 = off;     off += align_up(n_states * 272 * sizeof(float));
     w.kvfrag = off;   off += align_up(n_states * 2048);
@@ -181,6 +183,12 @@ int compute_units() {
     return cached;
 }
 }  // namespace msla
+
+namespace msla {
+int multiscale_state_small(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms, float* kv,
+                           void* scratch, size_t scratch_bytes, int B, int H, int W, int heads, int head_dim,
+                           const int* scales, int n_scales, int dt, hipStream_t stream);
+}
 
 extern "C" {
 
@@ -305,11 +313,13 @@ msla_status msla_forward_profiled(const void* x, const void* w_qkv, const void* 
                         head_dim, scales, n_scales, eps, dt, layout, stream, events, 0u);
 }
 
-msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms_out,
-                                  float* kv, void* workspace, size_t workspace_bytes, int B, int H, int W,
-                                  int heads, int head_dim, const int* scales, int n_scales, msla_dtype dt,
-                                  void* stream) {
-    if (!qkv || !workspace || !kv) return MSLA_ERR_INVALID_ARG;
+// Shared by msla_multiscale_state and its allocation-free variant: `small` says that `workspace`
+// holds only the per-state buffers (then q_ms_out must be given).
+static msla_status multiscale_state_impl(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms_out,
+                                         float* kv, void* workspace, size_t workspace_bytes, int B, int H, int W,
+                                         int heads, int head_dim, const int* scales, int n_scales, msla_dtype dt,
+                                         void* stream, bool small) {
+    if (!qkv || !workspace || !kv || (small && !q_ms_out)) return MSLA_ERR_INVALID_ARG;
     if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
     if (!aligned16(qkv) || !aligned16(workspace) || !aligned16(w_dw) || !aligned16(w_gpw) ||
         !aligned16(q_ms_out) || !aligned16(kv))
@@ -317,7 +327,7 @@ msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void*
     Shape s;
     msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
     if (st != MSLA_OK) return st;
-    const Workspace wo = carve(s, dt);
+    const Workspace wo = carve(s, dt, !small);
     if (workspace_bytes < wo.total) return MSLA_ERR_WORKSPACE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
@@ -331,6 +341,14 @@ msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void*
     if (hipMemcpyAsync(kv, ws + wo.kv32, n_states * 272 * sizeof(float), hipMemcpyDeviceToDevice, hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     return MSLA_OK;
+}
+
+msla_status msla_multiscale_state(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms_out,
+                                  float* kv, void* workspace, size_t workspace_bytes, int B, int H, int W,
+                                  int heads, int head_dim, const int* scales, int n_scales, msla_dtype dt,
+                                  void* stream) {
+    return multiscale_state_impl(qkv, w_dw, w_gpw, q_ms_out, kv, workspace, workspace_bytes, B, H, W, heads,
+                                 head_dim, scales, n_scales, dt, stream, /*small=*/false);
 }
 
 msla_status msla_core_forward(const void* qkv, const void* w_dw, const void* w_gpw, void* att, void* workspace,
@@ -372,3 +390,11 @@ msla_status msla_linear(const void* x, const void* w, void* y, long n_tokens, in
 }
 
 }  // extern "C"
+
+int msla::multiscale_state_small(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms, float* kv,
+                                 void* scratch, size_t scratch_bytes, int B, int H, int W, int heads,
+                                 int head_dim, const int* scales, int n_scales, int dt, hipStream_t stream) {
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    return multiscale_state_impl(qkv, w_dw, w_gpw, q_ms, kv, scratch, scratch_bytes, B, H, W, heads, head_dim,
+                                 scales, n_scales, (msla_dtype)dt, stream, /*small=*/true);
+}

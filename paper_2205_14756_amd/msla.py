@@ -31,7 +31,7 @@ MSLA_OPT_STAGE_PROJECT, MSLA_OPT_STAGE_AGGREGATE, MSLA_OPT_STAGE_FINALIZE, MSLA_
 
 EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
            "msla_core_forward",
-           "msla_multiscale_state", "msla_linear")
+           "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear")
 
 _DTYPES = {torch.float32: MSLA_F32, torch.float16: MSLA_F16, torch.bfloat16: MSLA_BF16}
 
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.msla_core_forward.restype = i
     lib.msla_multiscale_state.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, ip, i, i, vp]
     lib.msla_multiscale_state.restype = i
+    lib.msla_multiscale_state_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ip, i, i, vp]
+    lib.msla_multiscale_state_static.restype = i
     lib.msla_linear.argtypes = [vp, vp, vp, ctypes.c_long, i, i, i, vp]
     lib.msla_linear.restype = i
     _lib = lib
@@ -204,6 +206,20 @@ def msla_multiscale_state(qkv, w_dw, w_gpw, heads, head_dim, scales, workspace=N
                                               sc, ns, _DTYPES[qkv.dtype], _stream(stream))
     if st != MSLA_OK:
         raise MslaError(st, "msla_multiscale_state")
+    return q_ms, kv
+
+
+def msla_multiscale_state_static(qkv, w_dw, w_gpw, heads, head_dim, scales, q_ms, kv, stream=None):
+    """msla_multiscale_state without a workspace and without any allocation: the caller passes the
+    outputs q_ms [B,H,W,S*Ct] and kv [B,S,heads,d,d+1] fp32; the library's own device array is the scratch."""
+    _dev(qkv, w_dw, w_gpw, q_ms, kv)
+    B, H, W, ch = qkv.shape
+    sc, ns = _scales(scales)
+    st = load_library().msla_multiscale_state_static(_ptr(qkv), _ptr(w_dw), _ptr(w_gpw), _ptr(q_ms), _ptr(kv),
+                                                     B, H, W, heads, head_dim, sc, ns, _DTYPES[qkv.dtype],
+                                                     _stream(stream))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_multiscale_state_static")
     return q_ms, kv
 
 
