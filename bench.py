@@ -6,9 +6,16 @@ aggregation + Eq. (3) state, fused normalise-and-apply + output projection)
 over one batch of synthetic input that is already resident in HBM.
 
 Prints ONE JSON line: whole-job tokens/s on the headline workload (8 x 256 x
-64 x 128 tokens, fp16, scales {raw, 5x5}, 10 % zeros), the roofline of the
-dominant kernel measured live with HIP events on the launch stream, and the
-fp64 CPU oracle timed on the host cores as a reported baseline.
+64 x 128 tokens, fp16, scales {raw, 5x5}, 10 % zeros) over exactly --steps
+steps after --warmup steps; the same at steady clocks (a disclosed second loop
+behind a busy prelude); the duration of every stage, each timed alone with HIP
+events on the launch stream; the roofline of the dominant kernel; the other
+workloads and the module without its projections; and the fp64 CPU oracle
+timed on the host cores as a reported baseline.  Exits non-zero when the
+benchmarked output misses the parity bar against the plain oracle.
+
+`python bench.py --copy-probe` runs only a device copy of known size (the calibration run for the
+rocprofv3 FETCH_SIZE / WRITE_SIZE summaries under profiles/).
 """
 from __future__ import annotations
 
@@ -25,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
+TOL = {"f32": 1e-4, "f16": 5e-3, "bf16": 5e-3}
 
 STAGES = ("qkv_project", "aggregate_state", "state_finalize", "apply_project")
 
@@ -44,6 +52,7 @@ class HipEvents:
     def __init__(self, n: int):
         self.hip = _hip()
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
@@ -55,15 +64,17 @@ class HipEvents:
                 raise RuntimeError(f"hipEventCreate failed: {rc}")
             self.handles.append(h.value)
 
+    def record(self, i: int, stream):
+        rc = self.hip.hipEventRecord(self.handles[i], ctypes.c_void_p(stream.cuda_stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
     def elapsed_ms(self, i: int, j: int) -> float:
         ms = ctypes.c_float()
         rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j])
         if rc != 0:
             raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
         return float(ms.value)
-
-    def sync(self, i: int):
-        self.hip.hipEventSynchronize(self.handles[i])
 
     def destroy(self):
         for h in self.handles:
@@ -83,18 +94,33 @@ def stage_algorithmic_bytes(wl) -> dict:
             "apply_project": (2 + A) * unit}
 
 
-def read_traffic(path: str, kernel: str):
-    """Optional measured HBM traffic (bytes per launch) from a rocprofv3 --pmc summary:
-    a line 'TRAFFIC_BYTES_PER_LAUNCH <stage> <bytes>'."""
+def read_profile_lines(path: str, key: str) -> dict:
+    """Lines '<key> <name> <number>' of a committed rocprofv3 summary -> {name: number}."""
+    found = {}
     try:
         with open(path) as f:
             for line in f:
-                m = re.match(r"TRAFFIC_BYTES_PER_LAUNCH\s+(\S+)\s+([0-9.eE+]+)", line.strip())
-                if m and m.group(1) == kernel:
-                    return float(m.group(2))
+                m = re.match(rf"{key}\s+(\S+)\s+([0-9.eE+-]+)", line.strip())
+                if m:
+                    found[m.group(1)] = float(m.group(2))
     except OSError:
         pass
-    return None
+    return found
+
+
+def copy_probe():
+    """A device-to-device copy of 256 MiB, four times: the known-size kernel that the FETCH_SIZE /
+    WRITE_SIZE readings of the module's kernels are scaled by."""
+    import torch
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(3)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe_bytes_read_per_launch": n, "copy_probe_bytes_written_per_launch": n, "launches": 4}))
 
 
 def main():
@@ -107,7 +133,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--workload", type=int, default=5, help="index into workloads.WORKLOADS (5 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_cfg5.txt"))
+    ap.add_argument("--no-other-workloads", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true")
+    ap.add_argument("--profiles", default=os.path.join(ROOT, "profiles"))
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the module is a single-device kernel path that "
@@ -120,44 +148,88 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.copy_probe:
+        copy_probe()
+        return
     msla.load_library()            # fails loudly if the HIP library is missing
-    wl = wk.WORKLOADS[args.workload]
-    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype]
-    t = wk.make_inputs(wl)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(tdt).cuda().contiguous()
-    x, w_qkv, w_proj = dev(t["x"]), dev(t["w_qkv"]), dev(t["w_proj"])
-    w_dw = dev(t["w_dw"]) if wl.scales else None
-    w_gpw = dev(t["w_gpw"]) if wl.scales else None
-    out = torch.empty_like(x)
-    ws = msla.new_workspace(wl.B, wl.C, wl.H, wl.W, wl.heads, wl.head_dim, wl.scales, tdt)
     stream = torch.cuda.current_stream()
+    tdt_of = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
-    def step():
-        msla.msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, wl.heads, wl.head_dim, wl.scales, wl.eps,
-                          out=out, workspace=ws, stream=stream)
+    class Resident:
+        """One workload's tensors in HBM + its workspace and output."""
 
+        def __init__(self, wl):
+            self.wl = wl
+            self.t = wk.make_inputs(wl)
+            tdt = tdt_of[wl.dtype]
+            dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(tdt).cuda().contiguous()
+            self.x, self.w_qkv, self.w_proj = dev(self.t["x"]), dev(self.t["w_qkv"]), dev(self.t["w_proj"])
+            self.w_dw = dev(self.t["w_dw"]) if wl.scales else None
+            self.w_gpw = dev(self.t["w_gpw"]) if wl.scales else None
+            self.out = torch.empty_like(self.x)
+            self.ws = msla.new_workspace(wl.B, wl.C, wl.H, wl.W, wl.heads, wl.head_dim, wl.scales, tdt)
+
+        def step(self, options=0):
+            wl = self.wl
+            msla.msla_forward(self.x, self.w_qkv, self.w_dw, self.w_gpw, self.w_proj, wl.heads, wl.head_dim,
+                              wl.scales, wl.eps, out=self.out, workspace=self.ws, stream=stream, options=options)
+
+    def timed(fn, n):
+        """n calls of fn, synchronise-bracketed wall clock: ms per call."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    wl = wk.WORKLOADS[args.workload]
+    r = Resident(wl)
+
+    # ---- the contract's figure: W untimed steps, then exactly K timed ones
     for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    tokens_per_s = wl.tokens * args.steps / elapsed
+        r.step()
+    ms_per_step = timed(r.step, args.steps)
+    tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
 
-    # ---- per-stage durations: the same K steps again, with HIP events recorded on the launch
-    # stream between the stages (kept out of the loop above so they cannot perturb `value`)
-    # An event between two kernels keeps the second from starting while the first drains, so the
-    # intervals between the events add up to more than the step timed above without them.  That
-    # excess, shared equally between the stages, is taken off each interval: the stage times then
-    # add up to the measured step (the raw intervals are reported too).
-    n_staged = min(args.steps, 500)
+    # ---- the same at steady clocks: a busy prelude of at least 60 ms of these same steps, then a
+    # loop of at least 2000 steps (a board that has been idle needs ~25 ms of work to leave its idle
+    # clocks, so a short --warmup times the ramp)
+    prelude = max(600, int(60.0 / max(ms_per_step, 1e-3)))
+    for _ in range(prelude):
+        r.step()
+    n_steady = max(args.steps, 2000)
+    ms_steady = timed(r.step, n_steady)
+
+    # ---- every stage alone: n launches of that stage's kernel(s) back to back between two HIP events
+    # on the launch stream (the workspace holds what a complete step left there).  No event sits
+    # between two different kernels, so nothing is corrected; consecutive launches of one kernel
+    # overlap their tails and heads as consecutive kernels of a step do.
+    bits = {"qkv_project": msla.MSLA_OPT_STAGE_PROJECT, "aggregate_state": msla.MSLA_OPT_STAGE_AGGREGATE,
+            "state_finalize": msla.MSLA_OPT_STAGE_FINALIZE, "apply_project": msla.MSLA_OPT_STAGE_APPLY}
+    n_alone = 400
+    ev = HipEvents(2)
+    stage_ms = {}
+    for s in STAGES:
+        for _ in range(50):
+            r.step(bits[s])
+        ev.record(0, stream)
+        for _ in range(n_alone):
+            r.step(bits[s])
+        ev.record(1, stream)
+        torch.cuda.synchronize()
+        stage_ms[s] = ev.elapsed_ms(0, 1) / n_alone
+    ev.destroy()
+    r.step()                                     # leave a complete step's output behind for the parity check
+
+    # ---- the stages inside whole steps: HIP events recorded between the kernels by the library.  An
+    # event between two kernels keeps the second from starting while the first drains, so these
+    # intervals add up to more than a step; they are reported as measured.
+    n_staged = 300
     ev = HipEvents(5 * n_staged)
     for i in range(n_staged):
-        msla.msla_forward_profiled(x, w_qkv, w_dw, w_gpw, w_proj, wl.heads, wl.head_dim, wl.scales, wl.eps,
-                                   out, ws, ev.handles[5 * i:5 * i + 5], stream=stream)
+        msla.msla_forward_profiled(r.x, r.w_qkv, r.w_dw, r.w_gpw, r.w_proj, wl.heads, wl.head_dim, wl.scales,
+                                   wl.eps, r.out, r.ws, ev.handles[5 * i:5 * i + 5], stream=stream)
     torch.cuda.synchronize()
     stage_raw = {s: 0.0 for s in STAGES}
     for i in range(n_staged):
@@ -165,8 +237,7 @@ def main():
             stage_raw[s] += ev.elapsed_ms(5 * i + j, 5 * i + j + 1)
     ev.destroy()
     stage_raw = {s: v / n_staged for s, v in stage_raw.items()}
-    event_ms = max(sum(stage_raw.values()) - ms_per_step, 0.0) / len(STAGES)
-    stage_ms = {s: max(v - event_ms, 0.0) for s, v in stage_raw.items()}
+
     # ---- the practical ceiling: a plain device-to-device copy well beyond the memory-side cache
     # (512 MiB read + 512 MiB written per copy), timed with events on the same stream
     n_copy = 512 << 20
@@ -187,22 +258,66 @@ def main():
     alg = stage_algorithmic_bytes(wl)
     dominant = max(STAGES, key=lambda s: stage_ms[s])
     achieved = alg[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    frac_of = lambda ms, core=False: round(wl.algorithmic_bytes(core) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    tag = f"cfg{args.workload}"
+    traffic = read_profile_lines(os.path.join(args.profiles, f"hbm_traffic_{tag}.txt"), "TRAFFIC_BYTES_PER_LAUNCH")
+    mfma = read_profile_lines(os.path.join(args.profiles, f"mfma_util_{tag}.txt"), "MFMA_UTIL")
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(args.traffic_file, dominant),
+                "traffic": traffic.get(dominant),
+                "traffic_source": "committed rocprofv3 --pmc summary under profiles/ (fabric-side bytes, not this run)",
                 "algorithmic_bytes": alg[dominant], "avg_ms": round(stage_ms[dominant], 5),
                 "stage_ms": {s: round(v, 5) for s, v in stage_ms.items()},
+                "stage_ms_method": f"each stage alone, {n_alone} launches between two HIP events on the launch stream, uncorrected",
+                "stage_frac": {s: round(alg[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for s in STAGES if alg[s]},
                 "stage_event_interval_ms": {s: round(v, 5) for s, v in stage_raw.items()},
-                "event_cost_per_stage_ms": round(event_ms, 5),
+                "mfma_util": mfma or None,
+                "mfma_util_source": "SQ_VALU_MFMA_BUSY_CYCLES / (4 * SQ_BUSY_CU_CYCLES) from the committed --pmc summary",
                 "module_algorithmic_bytes": wl.algorithmic_bytes(),
-                "module_frac": round(wl.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "module_frac": frac_of(ms_per_step),
+                "ms_per_step_steady": round(ms_steady, 5),
+                "steady_loop": f"{n_steady} steps after a busy prelude of {prelude} steps",
+                "module_frac_steady": frac_of(ms_steady),
                 "measured_copy_gbs": round(copy_gbs, 1)}
+
+    # ---- the other workloads, and the module without its projections on the headline workload:
+    # steady-state ms per module, tokens/s and fraction of the HBM roofline on their own algorithmic bytes
+    others = None
+    if not args.no_other_workloads:
+        others = {}
+        for i, owl in sorted(wk.WORKLOADS.items()):
+            if i == args.workload:
+                continue
+            o = Resident(owl)
+            for _ in range(400):
+                o.step()
+            ms = timed(o.step, 1500)
+            others[owl.name] = {"entry": "msla_forward", "dtype": owl.dtype, "tokens": owl.tokens,
+                                "ms_per_module": round(ms, 5), "tokens_per_s": round(owl.tokens / (ms * 1e-3), 1),
+                                "module_frac": round(owl.algorithmic_bytes() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del o
+        qkv = msla.msla_linear(r.x, r.w_qkv)
+        att = torch.empty((wl.B, wl.H, wl.W, wl.branches * wl.heads * wl.head_dim), dtype=qkv.dtype, device="cuda")
+        core = lambda: msla.msla_core_forward(qkv, r.w_dw, r.w_gpw, wl.heads, wl.head_dim, wl.scales, wl.eps,
+                                              att=att, workspace=r.ws, stream=stream)
+        for _ in range(400):
+            core()
+        ms = timed(core, 1500)
+        others[wl.name + ":core"] = {"entry": "msla_core_forward", "dtype": wl.dtype, "tokens": wl.tokens,
+                                     "ms_per_module": round(ms, 5), "tokens_per_s": round(wl.tokens / (ms * 1e-3), 1),
+                                     "module_frac": frac_of(ms, True),
+                                     "note": "materialises the attention map; priced on the fused core's 5+3A units"}
+        del qkv, att
+        r.step()
+        torch.cuda.synchronize()
 
     # ---- the fp64 CPU oracle as it stands, on the host cores (reported baseline + parity check)
     cpu = None
     parity = None
+    failed = False
     if not args.no_cpu_baseline:
         from oracle import msla_oracle as orc
+        t = r.t
         # whole passes over the full batch until about ten seconds of CPU work have been timed
         passes, cpu_s = 0, 0.0
         while cpu_s < 10.0:
@@ -214,34 +329,30 @@ def main():
         cpu = {"value": round(wl.tokens * passes / cpu_s, 1), "unit": "tokens/s", "cores": orc.num_threads(),
                "kind": "oracle", "sample": f"{passes} passes over the full {wl.name} batch ({wl.tokens} tokens "
                                             f"each), {cpu_s:.2f} s wall in total"}
-        # Parity of the benchmarked output against the plain fp64 oracle (untimed).  Eq. (3) is
-        # discontinuous where a token's rectified Q row is all zero (0/0 vs. a unit-size quotient),
-        # so a token whose only positive Q component is within a few roundoffs of zero may flip
-        # under 16-bit storage; the figure is reported over all tokens and over the tokens whose
-        # gate margin is at least 64 unit roundoffs.
-        got = out.to(torch.float64).cpu().numpy()
-        err = np.abs(got - ref).reshape(wl.B * wl.H * wl.W, -1).max(-1)
-        scale = np.abs(ref).max()
-        _, parts = orc.forward_staged(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], wl.heads,
-                                      wl.head_dim, wl.scales, wl.eps, return_parts=True)
-        margin = orc.gate_margin(parts["q_tokens"], parts["kv"], wl.heads, wl.head_dim).min(-1).reshape(-1)
-        unit_roundoff = {"f32": 2.0 ** -24, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[wl.dtype]
-        well = margin >= 64 * unit_roundoff
-        parity = {"all_tokens": float(err.max() / scale),
-                  "gate_conditioned": float(err[well].max() / scale) if well.any() else 0.0,
-                  "gate_conditioned_fraction": float(well.mean())}
+        # Parity of the benchmarked output against the plain fp64 oracle (untimed), every token.
+        got = r.out.to(torch.float64).cpu().numpy()
+        err = np.abs(got - ref).reshape(wl.tokens, -1).max(-1) / np.abs(ref).max()
+        over = int((err > TOL[wl.dtype]).sum())
+        parity = {"all_tokens": float(err.max()), "bar": TOL[wl.dtype], "tokens_over_bar": over,
+                  "finite": bool(np.isfinite(got).all())}
+        # (workload 4 holds one token at which Eq. (3) is ill-posed under bf16 storage; the tests judge it)
+        allowed = 1 if args.workload == 4 else 0
+        failed = over > allowed or not parity["finite"]
 
+    shape = f"{wl.B}x{wl.H}x{wl.W} tokens, C={wl.C}, {wl.dtype}" if args.workload != 5 else "64x128 tokens, C=256, fp16"
     line = {
-        "metric": "MSLA module tokens/s (64x128 tokens, C=256, fp16)", "value": round(tokens_per_s, 1),
+        "metric": f"MSLA module tokens/s ({shape})", "value": round(tokens_per_s, 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "C": wl.C, "H": wl.H, "W": wl.W, "heads": wl.heads,
                    "head_dim": wl.head_dim, "scales": ["raw"] + [f"{k}x{k}" for k in wl.scales],
                    "tokens": wl.tokens, "zero_frac": wl.zero_frac},
-        "roofline": roofline, "cpu_baseline": cpu, "max_err_over_max_out": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "max_err_over_max_out": parity, "other_workloads": others,
     }
     print(json.dumps(line))
+    if failed:
+        sys.exit(f"bench.py: the benchmarked output misses the parity bar: {parity}")
 
 
 if __name__ == "__main__":
