@@ -709,6 +709,10 @@ hipError_t launch_apply(int dt, const void* q_ms, const void* kvfrag, const floa
 hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
                                 const void* w_proj, void* out, long n_tokens, int tokens_per_image, int n_hb,
                                 int c_out, float eps, hipStream_t stream) {
+    // more head-branches than the register-resident form holds: the long-contraction kernel
+    if (n_hb > 32 && small_product(dt, n_tokens, n_hb * 16, c_out))
+        return launch_small_apply_project(dt, q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out,
+                                          eps, stream);
     switch (dt) {
         case 0: return run_apply_project<float>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
         case 1: return run_apply_project<_Float16>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);

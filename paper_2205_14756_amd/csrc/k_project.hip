@@ -593,6 +593,7 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
 
 hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out,
                          hipStream_t stream) {
+    if (small_product(dt, n_tokens, c_in, c_out)) return launch_small_linear(dt, x, w, y, n_tokens, c_in, c_out, stream);
     switch (dt) {
         case 0: return run_project<float>(x, w, n_tokens, c_in, c_out, PlainDest<float>{(float*)y, n_tokens, c_out}, stream);
         case 1: return run_project<_Float16>(x, w, n_tokens, c_in, c_out, PlainDest<_Float16>{(_Float16*)y, n_tokens, c_out}, stream);
@@ -622,6 +623,9 @@ hipError_t run_qkv_project(const void* x, const void* w_qkv, void* q_ms, long q_
 hipError_t launch_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
                               void* kv_raw, long kv_tok_stride, long kv_head_stride, long kv_span,
                               long n_tokens, int c_in, int heads, hipStream_t stream) {
+    if (small_product(dt, n_tokens, c_in, 3 * heads * 16))
+        return launch_small_qkv_project(dt, x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, n_tokens,
+                                        c_in, heads, stream);
     switch (dt) {
         case 0: return run_qkv_project<float>(x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, c_in, heads, stream);
         case 1: return run_qkv_project<_Float16>(x, w_qkv, q_ms, q_ms_stride, kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, c_in, heads, stream);

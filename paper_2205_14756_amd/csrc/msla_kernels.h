@@ -7,6 +7,9 @@
 
 namespace msla {
 
+// Number of compute units of the current device (queried once per process).
+int compute_units();
+
 // y[n, o] = sum_c x[n, c] * w[o, c]
 hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in,
                          int c_out, hipStream_t stream);
@@ -64,6 +67,22 @@ hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, co
                                 const void* w_proj, void* out, long n_tokens, int tokens_per_image,
                                 int n_hb, int c_out, float eps, hipStream_t stream);
 
+// The same three operations for 16-bit storage types with a contraction of 257 .. 1024 slots and
+// few enough tokens that the weights are what a workgroup mostly fetches (k_small.hip).  They return
+// hipErrorNotSupported, without launching, for anything else.
+hipError_t launch_small_linear(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out,
+                               hipStream_t stream);
+hipError_t launch_small_qkv_project(int dt, const void* x, const void* w_qkv, void* q_ms, long q_ms_stride,
+                                    void* kv_raw, long kv_tok_stride, long kv_head_stride, long n_tokens, int c_in,
+                                    int heads, hipStream_t stream);
+hipError_t launch_small_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
+                                      const void* w_proj, void* out, long n_tokens, int tokens_per_image, int n_hb,
+                                      int c_out, float eps, hipStream_t stream);
+// whether a [n_tokens x K] by [K x c_out] product is "small" in that sense
+inline bool small_product(int dt, long n_tokens, int K, int c_out) {
+    return dt != 0 && K > 256 && K <= 1024 && ((n_tokens + 31) / 32) * ((c_out + 127) / 128) <= 8L * compute_units();
+}
+
 // dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);
@@ -82,9 +101,6 @@ inline hipError_t allow_dynamic_lds(int bytes) {
     if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
     return e;
 }
-
-// Number of compute units of the current device (queried once per process).
-int compute_units();
 
 constexpr int kAggTileH = 8;        // vector-ALU kernel (fp32 storage)
 constexpr int kAggTileW = 32;

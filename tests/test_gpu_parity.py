@@ -210,6 +210,10 @@ def test_multiscale_state_and_core(dtype, B, H, W, heads, scales):
     (1, 272, 17, 40, 17, (5,)),     # more than one output-channel block in the projection
     (1, 48, 12, 20, 2, (5,)),       # C != heads * head_dim: narrower attention than the module
     (2, 32, 9, 31, 4, (3,)),        # ... and wider
+    (1, 272, 9, 13, 17, (3, 5)),    # 51 head-branches (816 contraction slots), 272 input channels: long-contraction kernels
+    (2, 512, 7, 9, 32, (5,)),       # 64 head-branches (1024 slots), 512 input channels
+    (1, 384, 6, 11, 24, (5,)),      # 48 head-branches (768 slots), ragged 32-token tiles
+    (1, 640, 5, 8, 40, (5,)),       # 80 head-branches: beyond the long-contraction kernel, tiled forms
 ])
 def test_forward_small(dtype, B, C, H, W, heads, scales):
     d = 16
