@@ -134,7 +134,12 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="index into workloads.WORKLOADS (5 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="only the contract's loop: no steady loop, stage timing or copy ceiling (for counter runs)")
     ap.add_argument("--copy-probe", action="store_true")
+    ap.add_argument("--state-ab", action="store_true",
+                    help="only time the raw-branch Eq. (3) state of the headline shape on the matrix cores "
+                         "against the vector-ALU + shuffle form")
     ap.add_argument("--profiles", default=os.path.join(ROOT, "profiles"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -183,6 +188,37 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
+    if args.state_ab:
+        # The [d x N].[N x (d+1)] contraction of Eq. (3), raw branch only (no aggregated scale, so the
+        # kernel does nothing else), headline shape: same launch geometry, same loads, the two ways
+        # of doing the arithmetic.  Each timed alone, 400 launches between two HIP events.
+        import dataclasses
+        raw = dataclasses.replace(wk.WORKLOADS[5], name="cfg5_raw_branch_only", scales=())
+        r = Resident(raw)
+        res = {}
+        for name, opt in (("mfma", 0), ("valu_shuffle", msla.MSLA_OPT_STATE_VALU)):
+            r.step(opt)
+            torch.cuda.synchronize()
+            res[name + "_out"] = r.out.clone()
+            ev = HipEvents(2)
+            for _ in range(300):
+                r.step(opt | msla.MSLA_OPT_STAGE_AGGREGATE)
+            ev.record(0, stream)
+            for _ in range(400):
+                r.step(opt | msla.MSLA_OPT_STAGE_AGGREGATE)
+            ev.record(1, stream)
+            torch.cuda.synchronize()
+            res[name] = ev.elapsed_ms(0, 1) / 400
+            ev.destroy()
+        diff = float((res["mfma_out"].double() - res["valu_shuffle_out"].double()).abs().max() /
+                     res["mfma_out"].double().abs().max())
+        kv_bytes = 2 * raw.elem_bytes * raw.heads * raw.head_dim * raw.tokens
+        print(json.dumps({"state_ab": {"workload": raw.name, "bytes_read_per_launch": kv_bytes,
+                                       "mfma_ms": round(res["mfma"], 5), "valu_shuffle_ms": round(res["valu_shuffle"], 5),
+                                       "mfma_gbs": round(kv_bytes / res["mfma"] / 1e6, 1),
+                                       "valu_shuffle_gbs": round(kv_bytes / res["valu_shuffle"] / 1e6, 1),
+                                       "max_rel_diff_of_module_outputs": diff}}))
+        return
     wl = wk.WORKLOADS[args.workload]
     r = Resident(wl)
 
@@ -192,72 +228,77 @@ def main():
     ms_per_step = timed(r.step, args.steps)
     tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
 
-    # ---- the same at steady clocks: a busy prelude of at least 60 ms of these same steps, then a
-    # loop of at least 2000 steps (a board that has been idle needs ~25 ms of work to leave its idle
-    # clocks, so a short --warmup times the ramp)
-    prelude = max(600, int(60.0 / max(ms_per_step, 1e-3)))
-    for _ in range(prelude):
-        r.step()
-    n_steady = max(args.steps, 2000)
-    ms_steady = timed(r.step, n_steady)
+    ms_steady, n_steady, prelude, n_alone = ms_per_step, 0, 0, 0
+    stage_ms = {s_: 0.0 for s_ in STAGES}
+    stage_raw = dict(stage_ms)
+    copy_gbs = 0.0
+    if not args.no_extra:
+        # ---- the same at steady clocks: a busy prelude of at least 60 ms of these same steps, then a
+        # loop of at least 2000 steps (a board that has been idle needs ~25 ms of work to leave its idle
+        # clocks, so a short --warmup times the ramp)
+        prelude = max(600, int(60.0 / max(ms_per_step, 1e-3)))
+        for _ in range(prelude):
+            r.step()
+        n_steady = max(args.steps, 2000)
+        ms_steady = timed(r.step, n_steady)
 
-    # ---- every stage alone: n launches of that stage's kernel(s) back to back between two HIP events
-    # on the launch stream (the workspace holds what a complete step left there).  No event sits
-    # between two different kernels, so nothing is corrected; consecutive launches of one kernel
-    # overlap their tails and heads as consecutive kernels of a step do.
-    bits = {"qkv_project": msla.MSLA_OPT_STAGE_PROJECT, "aggregate_state": msla.MSLA_OPT_STAGE_AGGREGATE,
-            "state_finalize": msla.MSLA_OPT_STAGE_FINALIZE, "apply_project": msla.MSLA_OPT_STAGE_APPLY}
-    n_alone = 400
-    ev = HipEvents(2)
-    stage_ms = {}
-    for s in STAGES:
-        for _ in range(50):
-            r.step(bits[s])
-        ev.record(0, stream)
-        for _ in range(n_alone):
-            r.step(bits[s])
-        ev.record(1, stream)
+        # ---- every stage alone: n launches of that stage's kernel(s) back to back between two HIP events
+        # on the launch stream (the workspace holds what a complete step left there).  No event sits
+        # between two different kernels, so nothing is corrected; consecutive launches of one kernel
+        # overlap their tails and heads as consecutive kernels of a step do.
+        bits = {"qkv_project": msla.MSLA_OPT_STAGE_PROJECT, "aggregate_state": msla.MSLA_OPT_STAGE_AGGREGATE,
+                "state_finalize": msla.MSLA_OPT_STAGE_FINALIZE, "apply_project": msla.MSLA_OPT_STAGE_APPLY}
+        n_alone = 400
+        ev = HipEvents(2)
+        stage_ms = {}
+        for s in STAGES:
+            for _ in range(50):
+                r.step(bits[s])
+            ev.record(0, stream)
+            for _ in range(n_alone):
+                r.step(bits[s])
+            ev.record(1, stream)
+            torch.cuda.synchronize()
+            stage_ms[s] = ev.elapsed_ms(0, 1) / n_alone
+        ev.destroy()
+        r.step()                                     # leave a complete step's output behind for the parity check
+
+        # ---- the stages inside whole steps: HIP events recorded between the kernels by the library.  An
+        # event between two kernels keeps the second from starting while the first drains, so these
+        # intervals add up to more than a step; they are reported as measured.
+        n_staged = 300
+        ev = HipEvents(5 * n_staged)
+        for i in range(n_staged):
+            msla.msla_forward_profiled(r.x, r.w_qkv, r.w_dw, r.w_gpw, r.w_proj, wl.heads, wl.head_dim, wl.scales,
+                                       wl.eps, r.out, r.ws, ev.handles[5 * i:5 * i + 5], stream=stream)
         torch.cuda.synchronize()
-        stage_ms[s] = ev.elapsed_ms(0, 1) / n_alone
-    ev.destroy()
-    r.step()                                     # leave a complete step's output behind for the parity check
+        stage_raw = {s: 0.0 for s in STAGES}
+        for i in range(n_staged):
+            for j, s in enumerate(STAGES):
+                stage_raw[s] += ev.elapsed_ms(5 * i + j, 5 * i + j + 1)
+        ev.destroy()
+        stage_raw = {s: v / n_staged for s, v in stage_raw.items()}
 
-    # ---- the stages inside whole steps: HIP events recorded between the kernels by the library.  An
-    # event between two kernels keeps the second from starting while the first drains, so these
-    # intervals add up to more than a step; they are reported as measured.
-    n_staged = 300
-    ev = HipEvents(5 * n_staged)
-    for i in range(n_staged):
-        msla.msla_forward_profiled(r.x, r.w_qkv, r.w_dw, r.w_gpw, r.w_proj, wl.heads, wl.head_dim, wl.scales,
-                                   wl.eps, r.out, r.ws, ev.handles[5 * i:5 * i + 5], stream=stream)
-    torch.cuda.synchronize()
-    stage_raw = {s: 0.0 for s in STAGES}
-    for i in range(n_staged):
-        for j, s in enumerate(STAGES):
-            stage_raw[s] += ev.elapsed_ms(5 * i + j, 5 * i + j + 1)
-    ev.destroy()
-    stage_raw = {s: v / n_staged for s, v in stage_raw.items()}
-
-    # ---- the practical ceiling: a plain device-to-device copy well beyond the memory-side cache
-    # (512 MiB read + 512 MiB written per copy), timed with events on the same stream
-    n_copy = 512 << 20
-    src = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
-    dst = torch.empty_like(src)
-    src.fill_(1)
-    for _ in range(2):
-        dst.copy_(src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(10):
-        dst.copy_(src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 2.0 * n_copy * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    del src, dst
+        # ---- the practical ceiling: a plain device-to-device copy well beyond the memory-side cache
+        # (512 MiB read + 512 MiB written per copy), timed with events on the same stream
+        n_copy = 512 << 20
+        src = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(2):
+            dst.copy_(src)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * n_copy * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+        del src, dst
 
     alg = stage_algorithmic_bytes(wl)
     dominant = max(STAGES, key=lambda s: stage_ms[s])
-    achieved = alg[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    achieved = alg[dominant] / (stage_ms[dominant] * 1e-3) / 1e9 if stage_ms[dominant] > 0 else 0.0
     frac_of = lambda ms, core=False: round(wl.algorithmic_bytes(core) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     tag = f"cfg{args.workload}"
     traffic = read_profile_lines(os.path.join(args.profiles, f"hbm_traffic_{tag}.txt"), "TRAFFIC_BYTES_PER_LAUNCH")
@@ -269,7 +310,7 @@ def main():
                 "algorithmic_bytes": alg[dominant], "avg_ms": round(stage_ms[dominant], 5),
                 "stage_ms": {s: round(v, 5) for s, v in stage_ms.items()},
                 "stage_ms_method": f"each stage alone, {n_alone} launches between two HIP events on the launch stream, uncorrected",
-                "stage_frac": {s: round(alg[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for s in STAGES if alg[s]},
+                "stage_frac": {s: round(alg[s] / (stage_ms[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for s in STAGES if alg[s] and stage_ms[s] > 0},
                 "stage_event_interval_ms": {s: round(v, 5) for s, v in stage_raw.items()},
                 "mfma_util": mfma or None,
                 "mfma_util_source": "SQ_VALU_MFMA_BUSY_CYCLES / (4 * SQ_BUSY_CU_CYCLES) from the committed --pmc summary",

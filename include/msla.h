@@ -99,6 +99,9 @@ msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw,
  *       depthwise) aggregation kernel instead of the matrix-core one.  msla_forward itself
  *       takes it only for an image whose maps span 2 GiB or more; this is how that path
  *       is reached at ordinary sizes.
+ *   MSLA_OPT_STATE_VALU  with n_scales == 0 (no aggregated scale) the Eq. (3) state is accumulated
+ *       on the vector ALUs with wavefront shuffles instead of the matrix cores (same result up to
+ *       summation order; kept so that the two can be timed against each other).  Ignored otherwise.
  *   MSLA_OPT_STAGE_PROJECT / _AGGREGATE / _FINALIZE / _APPLY  (for profiling) when any of these
  *       is set, only the kernels of the named stages are enqueued: the Q/K/V projection; the
  *       aggregation + partial Eq. (3) states; the fixed-order sum of the partial states; the
@@ -111,6 +114,7 @@ msla_status msla_forward(const void* x, const void* w_qkv, const void* w_dw,
 #define MSLA_OPT_STAGE_AGGREGATE 4u
 #define MSLA_OPT_STAGE_FINALIZE 8u
 #define MSLA_OPT_STAGE_APPLY 16u
+#define MSLA_OPT_STATE_VALU 32u
 msla_status msla_forward_opts(const void* x, const void* w_qkv, const void* w_dw,
                               const void* w_gpw, const void* w_proj, void* out,
                               void* workspace, size_t workspace_bytes,

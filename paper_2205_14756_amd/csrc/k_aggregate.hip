@@ -333,6 +333,93 @@ __global__ __launch_bounds__(kAggThreads) void raw_state_kernel(AggregateArgs a)
     }
 }
 
+// The same state without the matrix cores: wavefront-level outer products on the vector ALUs and a
+// shuffle reduction.  Four lanes share a token: lane (token slot l / 4, part p = l % 4) holds the
+// token's 16 rectified K channels and its V channels 4p..4p+3, and accumulates KV[e][4p + j] for all
+// e (64 fp32 sums) plus, in part 0's lanes, Ksum[e]; a wave takes 16 tokens per step.  At the end the
+// 16 token slots are summed with xor-shuffles and the four waves through LDS.  It exists so that the
+// choice of MFMA for this contraction can be measured (msla_forward_opts, MSLA_OPT_STATE_VALU).
+template <class T>
+__global__ __launch_bounds__(kAggThreads) void raw_state_valu_kernel(AggregateArgs a) {
+    typedef Traits<T> Tr;
+    typedef typename Tr::Frag Frag;
+    __shared__ float red[4 * kStateSize];
+    const unsigned Lid = xcd_remap(blockIdx.x, gridDim.x);
+    const int h = Lid % a.heads;
+    const int chunk = (Lid / a.heads) % a.nchunks;
+    const int b = Lid / (a.heads * a.nchunks);
+    const int Ct = a.heads * 16;
+    const long N = (long)a.H * a.W;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int slot = lane >> 2, p = lane & 3;
+    const T* qp = (const T*)a.q + (long)h * a.q_hs;
+    const T* kp = (const T*)a.k + (long)h * a.k_hs;
+    const T* vp = (const T*)a.v + (long)h * a.v_hs;
+    T* q_ms = (T*)a.q_ms;
+    const long q_ms_ts = (long)a.S * Ct;
+    float kv[16][4];
+    float ks[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        ks[e] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kv[e][j] = 0.f;
+    }
+    const long n_groups = (N + 15) / 16;
+    const long per_chunk = (long)a.tiles_per_chunk * 4;
+    const long g_begin = (long)chunk * per_chunk;
+    const long g_end = g_begin + per_chunk < n_groups ? g_begin + per_chunk : n_groups;
+    for (long g = g_begin + wave; g < g_end; g += 4) {
+        const long n = g * 16 + slot;
+        const long tok = (long)b * N + n;
+        Frag kf[4], vf = frag_zero<T>();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kf[i] = frag_zero<T>();
+        if (n < N) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) kf[i] = load_frag<T>(kp + tok * a.k_ts + i * 4);
+            vf = load_frag<T>(vp + tok * a.v_ts + p * 4);
+            if (a.copy_raw_q)
+                store_frag<T>(q_ms + tok * q_ms_ts + h * 16 + p * 4, load_frag<T>(qp + tok * a.q_ts + p * 4));
+        }
+        const f32x4 v4 = frag_to_f32<T>(vf);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x4 k4 = frag_to_f32<T>(frag_relu<T>(kf[i]));       // Eq. (2): relu(K)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                ks[i * 4 + r] += k4[r];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kv[i * 4 + r][j] = fmaf(k4[r], v4[j], kv[i * 4 + r][j]);
+            }
+        }
+    }
+    // sum over the 16 token slots of the wave (lanes that differ in bits 2..5)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+#pragma unroll
+        for (int o = 4; o < 64; o <<= 1) {
+            ks[e] += __shfl_xor(ks[e], o);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kv[e][j] += __shfl_xor(kv[e][j], o);
+        }
+    }
+    float* mine = red + wave * kStateSize;
+    if (slot == 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mine[e * 17 + p * 4 + j] = kv[e][j];
+            if (p == 0) mine[e * 17 + 16] = ks[e];
+        }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < kStateSize; j += kAggThreads) {
+        const float s = (red[j] + red[kStateSize + j]) + (red[2 * kStateSize + j] + red[3 * kStateSize + j]);
+        a.partials[((((long)b * a.S + 0) * a.heads + h) * a.nchunks + chunk) * kStateSize + j] = s;
+    }
+}
+
 // One workgroup per (image, branch, head): fixed-order sum of the partial
 // states, then the state as MFMA operands for the apply pass.  For the 16-bit
 // storage types the state is multiplied by a power of two that puts its
@@ -429,7 +516,10 @@ template <class T>
 hipError_t run_raw_state(const AggregateArgs& a, hipStream_t stream) {
     const long nblocks = (long)a.B * a.heads * a.nchunks;
     if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((raw_state_kernel<T>), dim3((unsigned)nblocks), dim3(kAggThreads), 0, stream, a);
+    if (a.state_valu)
+        hipLaunchKernelGGL((raw_state_valu_kernel<T>), dim3((unsigned)nblocks), dim3(kAggThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((raw_state_kernel<T>), dim3((unsigned)nblocks), dim3(kAggThreads), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -130,6 +130,7 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
     const bool aggregate = stage_wanted(options, MSLA_OPT_STAGE_AGGREGATE);
     if (s.n_scales == 0 && aggregate) {
         a.w_dw = nullptr; a.w_gpw = nullptr; a.ks = 0; a.branch = 0; a.do_raw = 1; a.copy_raw_q = copy_raw_q;
+        a.state_valu = (options & MSLA_OPT_STATE_VALU) ? 1 : 0;
         if (msla::launch_raw_state((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
     }
     for (int i = 0; i < s.n_scales && aggregate; ++i) {
@@ -220,7 +221,7 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
                                 float eps, msla_dtype dt, msla_layout layout, void* stream,
                                 void* const* events, unsigned options) {
     if (!x || !w_qkv || !w_proj || !out || !workspace || C <= 0) return MSLA_ERR_INVALID_ARG;
-    if (options & ~(MSLA_OPT_GENERAL_AGGREGATION | kStageBits)) return MSLA_ERR_INVALID_ARG;
+    if (options & ~(MSLA_OPT_GENERAL_AGGREGATION | MSLA_OPT_STATE_VALU | kStageBits)) return MSLA_ERR_INVALID_ARG;
     if ((options & kStageBits) && layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
     if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
     if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;

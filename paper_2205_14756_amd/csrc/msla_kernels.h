@@ -40,6 +40,7 @@ struct AggregateArgs {
     int nchunks, tiles_per_chunk;
     int do_raw;              // also accumulate the branch-0 state from the raw K, V
     int copy_raw_q;          // also copy the raw Q into the branch-0 columns of q_ms
+    int state_valu = 0;      // raw-state kernel only: vector ALUs + shuffles instead of the matrix cores
 };
 hipError_t launch_aggregate(int dt, const AggregateArgs& a, hipStream_t stream);
 

@@ -28,6 +28,7 @@ MSLA_NHWC, MSLA_NCHW = 0, 1
 
 MSLA_OPT_GENERAL_AGGREGATION = 1
 MSLA_OPT_STAGE_PROJECT, MSLA_OPT_STAGE_AGGREGATE, MSLA_OPT_STAGE_FINALIZE, MSLA_OPT_STAGE_APPLY = 2, 4, 8, 16
+MSLA_OPT_STATE_VALU = 32
 
 EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
            "msla_core_forward",

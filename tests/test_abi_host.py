@@ -158,5 +158,5 @@ def test_forward_opts_rejects_unknown_bits_and_stage_bits_with_nchw(lib):
     p = vp(0x1000)      # never dereferenced: every check below fails on the host
     call = lambda layout, opts: lib.msla_forward_opts(p, p, p, p, p, p, p, 1 << 40, 1, 64, 8, 8, 4, 16, sc, 1, 1e-15, F16,
                                                       layout, None, opts)
-    assert call(0, 32) == INVALID and call(0, 0x80000000) == INVALID
+    assert call(0, 64) == INVALID and call(0, 0x80000000) == INVALID
     assert call(1, 2) == UNSUPPORTED and call(1, 16 | 1) == UNSUPPORTED

@@ -303,6 +303,16 @@ def test_forward_general_aggregation_kernel_for_16_bit_types(dtype, B, C, H, W, 
     check_module(t, dtype, heads, d, scales, options=msla.MSLA_OPT_GENERAL_AGGREGATION, stages=False)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("B,C,H,W,heads", [(1, 32, 6, 6, 2), (2, 64, 96, 96, 4), (3, 80, 9, 20, 5)])
+def test_forward_raw_branch_state_on_the_vector_alus(dtype, B, C, H, W, heads):
+    """No aggregated scale, the Eq. (3) state accumulated with vector FMAs and wavefront shuffles
+    (MSLA_OPT_STATE_VALU) instead of the matrix cores: the same bar."""
+    print(f"forward, vector-ALU state: {dtype} B={B} C={C} {H}x{W} heads={heads}", flush=True)
+    t = wk.random_module(515 + C + H, dtype, B, C, H, W, heads, 16, ())
+    check_module(t, dtype, heads, 16, (), options=msla.MSLA_OPT_STATE_VALU, stages=False)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_forward_benchmark_configs_full_size(cfg):
     """The five workload shapes at full size, in the launch configuration the bench times."""
