@@ -125,3 +125,15 @@ def random_module(seed: int, dtype: str, B: int, C: int, H: int, W: int, heads: 
         mask = rng.random((B, H, W, 1)) < zero_token_frac
         t["x"] = np.where(mask, 0.0, t["x"])
     return t
+
+
+def ffn_weights(seed: int, dtype: str, C: int, hidden: int) -> Dict[str, np.ndarray]:
+    """Seeded weights of the FFN+DWConv half of the building block (the same recipe: N(0, 1/fan_in),
+    fan_in = C, 9 and hidden; rounded once to the storage dtype): w1 [hidden, C], w_ffn_dw [hidden, 3, 3],
+    w2 [C, hidden]."""
+    rng = np.random.default_rng(seed)
+    w1 = rng.standard_normal((hidden, C)) / np.sqrt(C)
+    w_dw = rng.standard_normal((hidden, 3, 3)) / 3.0
+    w2 = rng.standard_normal((C, hidden)) / np.sqrt(hidden)
+    r = lambda a: round_to_dtype(a, dtype)
+    return {"w1": r(w1), "w_ffn_dw": r(w_dw), "w2": r(w2)}
