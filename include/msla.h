@@ -73,6 +73,7 @@ typedef enum {
 
 typedef enum { MSLA_F32 = 0, MSLA_F16 = 1, MSLA_BF16 = 2 } msla_dtype;   /* storage type; sums are fp32 */
 typedef enum { MSLA_NHWC = 0, MSLA_NCHW = 1 } msla_layout;               /* of x and out */
+typedef enum { MSLA_ACT_RELU = 0, MSLA_ACT_HSWISH = 1 } msla_act;        /* hard-swish: a * clip(a + 3, 0, 6) / 6 */
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* msla_error_string(msla_status status);
@@ -178,6 +179,31 @@ msla_status msla_multiscale_state_static(const void* qkv, const void* w_dw, cons
                                          int B, int H, int W, int heads, int head_dim,
                                          const int* scales, int n_scales,
                                          msla_dtype dt, void* stream);
+
+/* The other half of the EfficientViT building block: the FFN with a depthwise convolution inserted
+ * (Section 3.1, "we insert a depthwise convolution in each FFN layer"; Fig. 2 left).  The paper's text
+ * gives no more than that; this library's declared reading is
+ *     h = act(W1 y)   1x1, C -> hidden        g = act(DW3x3(h))   stride 1, zero padding 1, cross-correlation
+ *     out = y + W2 g  1x1, hidden -> C, no activation, residual; no bias, no normalisation.
+ *   y, out [B, H, W, C] (token-major);  w1 [hidden, C];  w_dw [hidden, 3, 3];  w2 [C, hidden].
+ * C and hidden multiples of 16 (else MSLA_ERR_UNSUPPORTED).  out may not alias y.
+ * workspace: msla_ffn_workspace_bytes (two [B,H,W,hidden] maps). */
+msla_status msla_ffn_workspace_bytes(int B, int C, int H, int W, int hidden, msla_dtype dt, size_t* bytes);
+msla_status msla_ffn_forward(const void* y, const void* w1, const void* w_dw, const void* w2, void* out,
+                             void* workspace, size_t workspace_bytes,
+                             int B, int C, int H, int W, int hidden, msla_act act, msla_dtype dt, void* stream);
+
+/* The whole building block (Fig. 2 left; Section 3.2 puts it in stages 3 and 4 of the backbone):
+ *     y = x + MSLA(x)   (msla_forward, MSLA_NHWC)        out = y + FFN(y)   (msla_ffn_forward).
+ * Arguments as in those two calls (w_ffn_dw is the FFN's [hidden, 3, 3] filter).  out may not alias x. */
+msla_status msla_block_workspace_bytes(int B, int C, int H, int W, int heads, int head_dim,
+                                       const int* scales, int n_scales, int hidden, msla_dtype dt, size_t* bytes);
+msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                               const void* w_proj, const void* w1, const void* w_ffn_dw, const void* w2,
+                               void* out, void* workspace, size_t workspace_bytes,
+                               int B, int C, int H, int W, int heads, int head_dim,
+                               const int* scales, int n_scales, float eps,
+                               int hidden, msla_act act, msla_dtype dt, void* stream);
 
 /* Stage: a 1x1 projection of a token map (Section 3.1: Q = x W_Q etc., and the
  * final projection):  y[n, o] = sum_c x[n, c] * w[o, c],

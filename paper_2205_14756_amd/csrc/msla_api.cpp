@@ -379,6 +379,76 @@ msla_status msla_core_forward(const void* qkv, const void* w_dw, const void* w_g
     return MSLA_OK;
 }
 
+// ---- FFN+DWConv and the whole building block
+static bool ffn_shape_ok(int B, int C, int H, int W, int hidden) {
+    return B > 0 && C > 0 && H > 0 && W > 0 && hidden > 0;
+}
+static size_t ffn_ws_bytes(long T, int hidden, msla_dtype dt) { return 2 * align_up((size_t)T * hidden * elem_size(dt)); }
+
+msla_status msla_ffn_workspace_bytes(int B, int C, int H, int W, int hidden, msla_dtype dt, size_t* bytes) {
+    if (!bytes || !ffn_shape_ok(B, C, H, W, hidden)) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    if (C % 16 != 0 || hidden % 16 != 0 || (long)B * H * W > (1L << 31)) return MSLA_ERR_UNSUPPORTED;
+    *bytes = ffn_ws_bytes((long)B * H * W, hidden, dt);
+    return MSLA_OK;
+}
+
+msla_status msla_ffn_forward(const void* y, const void* w1, const void* w_dw, const void* w2, void* out,
+                             void* workspace, size_t workspace_bytes, int B, int C, int H, int W, int hidden,
+                             msla_act act, msla_dtype dt, void* stream) {
+    if (!y || !w1 || !w_dw || !w2 || !out || !workspace || !ffn_shape_ok(B, C, H, W, hidden)) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    if (act != MSLA_ACT_RELU && act != MSLA_ACT_HSWISH) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(y) || !aligned16(w1) || !aligned16(w_dw) || !aligned16(w2) || !aligned16(out) || !aligned16(workspace))
+        return MSLA_ERR_INVALID_ARG;
+    const long T = (long)B * H * W;
+    if (C % 16 != 0 || hidden % 16 != 0 || T > (1L << 31)) return MSLA_ERR_UNSUPPORTED;
+    if (workspace_bytes < ffn_ws_bytes(T, hidden, dt)) return MSLA_ERR_WORKSPACE;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* h_pre = static_cast<char*>(workspace);
+    char* g = h_pre + align_up((size_t)T * hidden * elem_size(dt));
+    if (msla::launch_linear((int)dt, y, w1, h_pre, T, C, hidden, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_ffn_dw((int)dt, h_pre, w_dw, g, B, H, W, hidden, (int)act, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_ffn_project((int)dt, g, w2, y, out, T, hidden, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+msla_status msla_block_workspace_bytes(int B, int C, int H, int W, int heads, int head_dim, const int* scales,
+                                       int n_scales, int hidden, msla_dtype dt, size_t* bytes) {
+    size_t a = 0, f = 0;
+    msla_status st = msla_workspace_bytes(B, C, H, W, heads, head_dim, scales, n_scales, dt, &a);
+    if (st != MSLA_OK) return st;
+    st = msla_ffn_workspace_bytes(B, C, H, W, hidden, dt, &f);
+    if (st != MSLA_OK) return st;
+    if (!bytes) return MSLA_ERR_INVALID_ARG;
+    // the attention module's workspace is dead once y = x + MSLA(x) exists, so the FFN reuses it
+    *bytes = align_up((size_t)B * H * W * C * elem_size(dt)) + (a > f ? a : f);
+    return MSLA_OK;
+}
+
+msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw,
+                               const void* w_proj, const void* w1, const void* w_ffn_dw, const void* w2, void* out,
+                               void* workspace, size_t workspace_bytes, int B, int C, int H, int W, int heads,
+                               int head_dim, const int* scales, int n_scales, float eps, int hidden, msla_act act,
+                               msla_dtype dt, void* stream) {
+    size_t need = 0;
+    const msla_status sz = msla_block_workspace_bytes(B, C, H, W, heads, head_dim, scales, n_scales, hidden, dt, &need);
+    if (sz != MSLA_OK) return sz;
+    if (!workspace || !x || !out || !w1 || !w_ffn_dw || !w2 || !aligned16(workspace)) return MSLA_ERR_INVALID_ARG;
+    if (act != MSLA_ACT_RELU && act != MSLA_ACT_HSWISH) return MSLA_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return MSLA_ERR_WORKSPACE;
+    const size_t y_bytes = align_up((size_t)B * H * W * C * elem_size(dt));
+    char* ybuf = static_cast<char*>(workspace);
+    char* rest = ybuf + y_bytes;
+    // MSLA(x) lands in `out`, which is free until the FFN's last kernel writes the block's result there
+    msla_status st = forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, rest, workspace_bytes - y_bytes, B, C, H, W, heads,
+                                  head_dim, scales, n_scales, eps, dt, MSLA_NHWC, stream, nullptr, 0u);
+    if (st != MSLA_OK) return st;
+    if (msla::launch_residual_add((int)dt, x, out, ybuf, (long)B * H * W * C, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return msla_ffn_forward(ybuf, w1, w_ffn_dw, w2, out, rest, workspace_bytes - y_bytes, B, C, H, W, hidden, act, dt, stream);
+}
+
 msla_status msla_linear(const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out,
                         msla_dtype dt, void* stream) {
     if (!x || !w || !y || n_tokens <= 0 || c_in <= 0 || c_out <= 0) return MSLA_ERR_INVALID_ARG;

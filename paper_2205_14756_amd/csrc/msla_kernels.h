@@ -84,6 +84,16 @@ inline bool small_product(int dt, long n_tokens, int K, int c_out) {
     return dt != 0 && K > 256 && K <= 1024 && ((n_tokens + 31) / 32) * ((c_out + 127) / 128) <= 8L * compute_units();
 }
 
+// The FFN+DWConv half of the building block (k_ffn.hip).  act: 0 ReLU, 1 hard-swish.
+//   g[b,y,x,c] = act(sum_{u,v} w_dw[c,u,v] * act(h[b, y+u-1, x+v-1, c]))     (zero outside the map)
+hipError_t launch_ffn_dw(int dt, const void* h, const void* w_dw, void* g, int B, int H, int W, int E, int act,
+                         hipStream_t stream);
+//   y = a + b (n_elems a multiple of 8)
+hipError_t launch_residual_add(int dt, const void* a, const void* b, void* y, long n_elems, hipStream_t stream);
+//   out[n, c] = res[n, c] + sum_e g[n, e] * w2[c, e]
+hipError_t launch_ffn_project(int dt, const void* g, const void* w2, const void* res, void* out, long n_tokens, int E,
+                              int c_out, hipStream_t stream);
+
 // dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);

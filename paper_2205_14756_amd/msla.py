@@ -32,7 +32,10 @@ MSLA_OPT_STATE_VALU = 32
 
 EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
            "msla_core_forward",
-           "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear")
+           "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear",
+           "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward")
+
+MSLA_ACT_RELU, MSLA_ACT_HSWISH = 0, 1
 
 _DTYPES = {torch.float32: MSLA_F32, torch.float16: MSLA_F16, torch.bfloat16: MSLA_BF16}
 
@@ -71,6 +74,14 @@ def load_library() -> ctypes.CDLL:
     lib.msla_multiscale_state.restype = i
     lib.msla_multiscale_state_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ip, i, i, vp]
     lib.msla_multiscale_state_static.restype = i
+    lib.msla_ffn_workspace_bytes.argtypes = [i, i, i, i, i, i, ctypes.POINTER(sz)]
+    lib.msla_ffn_workspace_bytes.restype = i
+    lib.msla_ffn_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
+    lib.msla_ffn_forward.restype = i
+    lib.msla_block_workspace_bytes.argtypes = [i, i, i, i, i, i, ip, i, i, i, ctypes.POINTER(sz)]
+    lib.msla_block_workspace_bytes.restype = i
+    lib.msla_block_forward.argtypes = [vp] * 10 + [sz, i, i, i, i, i, i, ip, i, f, i, i, i, vp]
+    lib.msla_block_forward.restype = i
     lib.msla_linear.argtypes = [vp, vp, vp, ctypes.c_long, i, i, i, vp]
     lib.msla_linear.restype = i
     _lib = lib
@@ -236,3 +247,59 @@ def msla_linear(x, w, y=None, stream=None):
     if st != MSLA_OK:
         raise MslaError(st, "msla_linear")
     return y
+
+
+def msla_ffn_workspace_bytes(B, C, H, W, hidden, dtype) -> int:
+    out = ctypes.c_size_t(0)
+    st = load_library().msla_ffn_workspace_bytes(B, C, H, W, hidden, _DTYPES[dtype], ctypes.byref(out))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_ffn_workspace_bytes")
+    return int(out.value)
+
+
+def msla_ffn_forward(y, w1, w_dw, w2, act=MSLA_ACT_RELU, out=None, workspace=None, stream=None):
+    """out = y + W2 . act(DW3x3(act(W1 . y))): y [B,H,W,C], w1 [hidden,C], w_dw [hidden,3,3], w2 [C,hidden]."""
+    _dev(y, w1, w_dw, w2, out, workspace)
+    B, H, W, C = y.shape
+    hidden = w1.shape[0]
+    if out is None:
+        out = torch.empty_like(y)
+    if workspace is None:
+        workspace = torch.empty(msla_ffn_workspace_bytes(B, C, H, W, hidden, y.dtype), dtype=torch.uint8, device=y.device)
+    st = load_library().msla_ffn_forward(_ptr(y), _ptr(w1), _ptr(w_dw), _ptr(w2), _ptr(out), _ptr(workspace),
+                                         workspace.numel(), B, C, H, W, hidden, int(act), _DTYPES[y.dtype],
+                                         _stream(stream))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_ffn_forward")
+    return out
+
+
+def msla_block_workspace_bytes(B, C, H, W, heads, head_dim, scales, hidden, dtype) -> int:
+    sc, ns = _scales(scales)
+    out = ctypes.c_size_t(0)
+    st = load_library().msla_block_workspace_bytes(B, C, H, W, heads, head_dim, sc, ns, hidden, _DTYPES[dtype],
+                                                   ctypes.byref(out))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_block_workspace_bytes")
+    return int(out.value)
+
+
+def msla_block_forward(x, w_qkv, w_dw, w_gpw, w_proj, w1, w_ffn_dw, w2, heads, head_dim, scales, eps=1e-15,
+                       act=MSLA_ACT_RELU, out=None, workspace=None, stream=None):
+    """The whole building block: y = x + MSLA(x); out = y + FFN(y).  x, out [B,H,W,C]."""
+    _dev(x, w_qkv, w_dw, w_gpw, w_proj, w1, w_ffn_dw, w2, out, workspace)
+    B, H, W, C = x.shape
+    hidden = w1.shape[0]
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(msla_block_workspace_bytes(B, C, H, W, heads, head_dim, scales, hidden, x.dtype),
+                                dtype=torch.uint8, device=x.device)
+    sc, ns = _scales(scales)
+    st = load_library().msla_block_forward(_ptr(x), _ptr(w_qkv), _ptr(w_dw), _ptr(w_gpw), _ptr(w_proj), _ptr(w1),
+                                           _ptr(w_ffn_dw), _ptr(w2), _ptr(out), _ptr(workspace), workspace.numel(),
+                                           B, C, H, W, heads, head_dim, sc, ns, float(eps), hidden, int(act),
+                                           _DTYPES[x.dtype], _stream(stream))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_block_forward")
+    return out
