@@ -349,6 +349,34 @@ def main():
                                      "module_frac": frac_of(ms, True),
                                      "note": "materialises the attention map; priced on the fused core's 5+3A units"}
         del qkv, att
+        # the other half of the building block on the headline shape (expansion 4, hard-swish): the FFN
+        # alone and the whole block.  Priced two ways: on the bytes of a fully fused FFN (read y, write
+        # out: 2 units of e*C*T) and on the bytes of the pipeline as built, which materialises the
+        # expanded map twice ((3 + 4*expansion) units).
+        hidden = 4 * wl.C
+        fw = wk.ffn_weights(wl.seed + 500, wl.dtype, wl.C, hidden)
+        fdev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(tdt_of[wl.dtype]).cuda().contiguous()
+        w1, wfd, w2 = fdev(fw["w1"]), fdev(fw["w_ffn_dw"]), fdev(fw["w2"])
+        bws = torch.empty(msla.msla_block_workspace_bytes(wl.B, wl.C, wl.H, wl.W, wl.heads, wl.head_dim, wl.scales, hidden,
+                                                          tdt_of[wl.dtype]), dtype=torch.uint8, device="cuda")
+        bout = torch.empty_like(r.x)
+        ffn = lambda: msla.msla_ffn_forward(r.x, w1, wfd, w2, msla.MSLA_ACT_HSWISH, out=bout, workspace=bws, stream=stream)
+        block = lambda: msla.msla_block_forward(r.x, r.w_qkv, r.w_dw, r.w_gpw, r.w_proj, w1, wfd, w2, wl.heads, wl.head_dim,
+                                                wl.scales, wl.eps, msla.MSLA_ACT_HSWISH, out=bout, workspace=bws, stream=stream)
+        unit = wl.elem_bytes * wl.C * wl.tokens
+        for name, fn, entry, fused_b, built_b in (
+                ("ffn", ffn, "msla_ffn_forward", 2 * unit, (3 + 4 * 4) * unit),
+                ("block", block, "msla_block_forward", wl.algorithmic_bytes() + 2 * unit,
+                 wl.algorithmic_bytes() + 3 * unit + (3 + 4 * 4) * unit)):
+            for _ in range(100):
+                fn()
+            ms = timed(fn, 300)
+            others[f"{wl.name}:{name}_hidden{hidden}_hswish"] = {
+                "entry": entry, "dtype": wl.dtype, "tokens": wl.tokens, "ms_per_module": round(ms, 5),
+                "tokens_per_s": round(wl.tokens / (ms * 1e-3), 1),
+                "frac_on_fused_bytes": round(fused_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "frac_on_bytes_as_built": round(built_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del w1, wfd, w2, bws, bout
         r.step()
         torch.cuda.synchronize()
 
