@@ -31,8 +31,11 @@ def test_rows_of_the_similarity_sum_to_one():
     perm = rng.permutation(N)
     assert np.allclose(sm.softmax_attention_head(Q, K[perm], V[perm]), O, atol=1e-12)
     # unlike the ReLU form it is NOT invariant to scaling Q and K: a large scale picks the best-matching key
-    big = sm.softmax_attention_head(200.0 * Q, K, V)
-    assert np.allclose(big, V[np.argmax(Q @ K.T, axis=1)], atol=1e-6)
+    big = sm.softmax_attention_head(2000.0 * Q, K, V)
+    scores = np.sort(Q @ K.T, axis=1)
+    clear = scores[:, -1] - scores[:, -2] > 0.05          # rows whose best key leads by a clear margin
+    assert clear.sum() > N // 2
+    assert np.allclose(big[clear], V[np.argmax(Q @ K.T, axis=1)][clear], atol=1e-6)
 
 
 def test_against_torch_scaled_dot_product_attention():
