@@ -377,6 +377,30 @@ def main():
                 "frac_on_fused_bytes": round(fused_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "frac_on_bytes_as_built": round(built_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del w1, wfd, w2, bws, bout
+        # Fig. 3 of the paper restated on this GPU: softmax attention (Eq. (1) with the exponential
+        # similarity) against ReLU linear attention (Eq. (3); msla_core_forward without aggregated scales)
+        # on the same projected maps, headline batch / heads / type, at three token counts.  The linear
+        # form's time grows with N, the softmax form's with N^2.
+        cmp = {}
+        for (hh, ww) in ((32, 32), (32, 64), (64, 128)):
+            n = hh * ww
+            q = torch.randn((wl.B, hh, ww, 3 * wl.heads * wl.head_dim), device="cuda").to(tdt_of[wl.dtype])
+            a1 = torch.empty((wl.B, hh, ww, wl.heads * wl.head_dim), dtype=q.dtype, device="cuda")
+            a2 = torch.empty_like(a1)
+            lws = msla.new_workspace(wl.B, wl.C, hh, ww, wl.heads, wl.head_dim, (), q.dtype)
+            lin = lambda: msla.msla_core_forward(q, None, None, wl.heads, wl.head_dim, (), wl.eps, att=a1, workspace=lws, stream=stream)
+            sm_ = lambda: msla.msla_softmax_attention(q, wl.heads, wl.head_dim, att=a2, stream=stream)
+            for _ in range(50):
+                lin()
+            t_lin = timed(lin, 300)
+            for _ in range(5):
+                sm_()
+            t_sm = timed(sm_, 30)
+            cmp[f"N={n}"] = {"relu_linear_ms": round(t_lin, 5), "softmax_ms": round(t_sm, 5), "softmax_over_linear": round(t_sm / t_lin, 1)}
+            del q, a1, a2, lws
+        others["softmax_vs_relu_linear"] = {"entry": "msla_softmax_attention vs msla_core_forward (no aggregated scale)",
+                                            "dtype": wl.dtype, "B": wl.B, "heads": wl.heads, "head_dim": wl.head_dim,
+                                            "per_token_count": cmp}
         r.step()
         torch.cuda.synchronize()
 

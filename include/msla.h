@@ -205,6 +205,16 @@ msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_d
                                const int* scales, int n_scales, float eps,
                                int hidden, msla_act act, msla_dtype dt, void* stream);
 
+/* Softmax attention, the form the paper's ReLU linear attention replaces (Section 3.1: Eq. (1) with
+ * Sim(Q, K) = exp(Q K^T / sqrt(d)); Fig. 3 compares the two): for every image and head
+ *     att_i = sum_j exp(Q_i . K_j / sqrt(d)) V_j / sum_j exp(Q_i . K_j / sqrt(d)).
+ *   qkv [B, N, 3*heads*head_dim] (channel order as everywhere: (h*3 + t)*head_dim + e)
+ *   att [B, N, heads*head_dim]
+ * Quadratic in N by definition; here as a measured comparison point (one pass over the keys, nothing of
+ * size N x N stored, fp32 sums).  head_dim == 16 only.  No workspace. */
+msla_status msla_softmax_attention(const void* qkv, void* att, int B, int N, int heads, int head_dim,
+                                   msla_dtype dt, void* stream);
+
 /* Stage: a 1x1 projection of a token map (Section 3.1: Q = x W_Q etc., and the
  * final projection):  y[n, o] = sum_c x[n, c] * w[o, c],
  *   x [n_tokens, c_in], w [c_out, c_in], y [n_tokens, c_out]; c_in, c_out multiples of 16. */

@@ -449,6 +449,17 @@ msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_d
     return msla_ffn_forward(ybuf, w1, w_ffn_dw, w2, out, rest, workspace_bytes - y_bytes, B, C, H, W, hidden, act, dt, stream);
 }
 
+msla_status msla_softmax_attention(const void* qkv, void* att, int B, int N, int heads, int head_dim, msla_dtype dt,
+                                   void* stream) {
+    if (!qkv || !att || B <= 0 || N <= 0 || heads <= 0 || head_dim <= 0) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(qkv) || !aligned16(att)) return MSLA_ERR_INVALID_ARG;
+    if (head_dim != 16 || (long)B * N > (1L << 31) || (long)heads * 16 > (1L << 20)) return MSLA_ERR_UNSUPPORTED;
+    if (msla::launch_softmax_attention((int)dt, qkv, att, B, N, heads, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
 msla_status msla_linear(const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out,
                         msla_dtype dt, void* stream) {
     if (!x || !w || !y || n_tokens <= 0 || c_in <= 0 || c_out <= 0) return MSLA_ERR_INVALID_ARG;

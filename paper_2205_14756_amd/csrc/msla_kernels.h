@@ -94,6 +94,9 @@ hipError_t launch_residual_add(int dt, const void* a, const void* b, void* y, lo
 hipError_t launch_ffn_project(int dt, const void* g, const void* w2, const void* res, void* out, long n_tokens, int E,
                               int c_out, hipStream_t stream);
 
+// Softmax attention per image and head on qkv [B, N, 3*heads*16] -> att [B, N, heads*16] (k_softmax.hip)
+hipError_t launch_softmax_attention(int dt, const void* qkv, void* att, int B, int N, int heads, hipStream_t stream);
+
 // dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);

@@ -33,7 +33,8 @@ MSLA_OPT_STATE_VALU = 32
 EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
            "msla_core_forward",
            "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear",
-           "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward")
+           "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward",
+           "msla_softmax_attention")
 
 MSLA_ACT_RELU, MSLA_ACT_HSWISH = 0, 1
 
@@ -82,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.msla_block_workspace_bytes.restype = i
     lib.msla_block_forward.argtypes = [vp] * 10 + [sz, i, i, i, i, i, i, ip, i, f, i, i, i, vp]
     lib.msla_block_forward.restype = i
+    lib.msla_softmax_attention.argtypes = [vp, vp, i, i, i, i, i, vp]
+    lib.msla_softmax_attention.restype = i
     lib.msla_linear.argtypes = [vp, vp, vp, ctypes.c_long, i, i, i, vp]
     lib.msla_linear.restype = i
     _lib = lib
@@ -303,3 +306,17 @@ def msla_block_forward(x, w_qkv, w_dw, w_gpw, w_proj, w1, w_ffn_dw, w2, heads, h
     if st != MSLA_OK:
         raise MslaError(st, "msla_block_forward")
     return out
+
+
+def msla_softmax_attention(qkv, heads, head_dim, att=None, stream=None):
+    """Softmax attention per image and head: qkv [B, ..., 3*heads*d] -> att [B, ..., heads*d]."""
+    _dev(qkv, att)
+    B = qkv.shape[0]
+    N = qkv.numel() // (B * qkv.shape[-1])
+    if att is None:
+        att = torch.empty(qkv.shape[:-1] + (heads * head_dim,), dtype=qkv.dtype, device=qkv.device)
+    st = load_library().msla_softmax_attention(_ptr(qkv), _ptr(att), B, N, heads, head_dim, _DTYPES[qkv.dtype],
+                                               _stream(stream))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_softmax_attention")
+    return att

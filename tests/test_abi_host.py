@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == {"msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_forward_opts", "msla_forward_profiled",
                           "msla_core_forward",
                           "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear",
-                          "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward"}
+                          "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward",
+                          "msla_softmax_attention"}
     for n in names:
         assert getattr(lib, n) is not None
     from paper_2205_14756_amd import msla
