@@ -366,8 +366,8 @@ def main():
         unit = wl.elem_bytes * wl.C * wl.tokens
         for name, fn, entry, fused_b, built_b in (
                 ("ffn", ffn, "msla_ffn_forward", 2 * unit, (3 + 4 * 4) * unit),
-                ("block", block, "msla_block_forward", wl.algorithmic_bytes() + 2 * unit,
-                 wl.algorithmic_bytes() + 3 * unit + (3 + 4 * 4) * unit)):
+                ("block", block, "msla_block_forward", wl.algorithmic_bytes() + 3 * unit,
+                 wl.algorithmic_bytes() + unit + (3 + 4 * 4) * unit)):
             for _ in range(100):
                 fn()
             ms = timed(fn, 300)

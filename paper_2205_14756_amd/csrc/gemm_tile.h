@@ -159,6 +159,59 @@ struct GemmTile {
             }
         }
     }
+
+    // The same with a residual: the wave parks its 16-token x 64-channel piece as fp32, each lane picks
+    // up the 16 output bytes it will write (8 or 4 channels), adds the residual's same 16 bytes
+    // (res(token row within the tile, channel) -> 16 bytes, zero past the ends) in fp32 and rounds
+    // once.  Needs kStageResBytes of LDS.
+    static constexpr int kStageResRow = 64 * 4 + 16;
+    static constexpr int kStageResWave = 16 * kStageResRow;
+    static constexpr int kStageResBytes = WR * WC * kStageResWave;
+    template <class TileOut, class Res>
+    static __device__ __forceinline__ void epilogue_lds_residual(const f32x4 (&acc)[4][4], char* stage, int oc0, int wr,
+                                                                 int wc, const TileOut& out, const Res& res) {
+        const int lane = lane_id();
+        const int x = lane & 15, q = lane >> 4;
+        char* mine = stage + (wr + WR * wc) * kStageResWave;
+        constexpr int kVecPerRow = 64 * (int)sizeof(T) / 16;        // 8 (16-bit) or 16 (fp32)
+        constexpr int kPer = 16 * kVecPerRow / 64;                  // output vectors per lane per piece
+        constexpr int kCh = Tr::kVec;                               // channels per output vector
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int io = 0; io < 4; ++io) *(f32x4*)(mine + x * kStageResRow + (io * 16 + q * 4) * 4) = acc[io][jt];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int v = lane + 64 * i;
+                const int row = v / kVecPerRow, cv = v % kVecPerRow;
+                const int trow = wc * 64 + jt * 16 + row, oc = oc0 + wr * 64 + cv * kCh;
+                const u32x4 r = res(trow, oc);
+                u32x4 val;
+                if constexpr (sizeof(T) == 4) {
+                    const f32x4 a = *(const f32x4*)(mine + row * kStageResRow + cv * 16);
+                    const f32x4 b = __builtin_bit_cast(f32x4, r);
+                    val = __builtin_bit_cast(u32x4, f32x4{a[0] + b[0], a[1] + b[1], a[2] + b[2], a[3] + b[3]});
+                } else {
+                    const f32x4 a0 = *(const f32x4*)(mine + row * kStageResRow + cv * 32);
+                    const f32x4 a1 = *(const f32x4*)(mine + row * kStageResRow + cv * 32 + 16);
+                    const Vec b = __builtin_bit_cast(Vec, r);
+                    Vec o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] = Tr::from_f32(a0[e] + Tr::to_f32(b[e]));
+                        o[4 + e] = Tr::from_f32(a1[e] + Tr::to_f32(b[4 + e]));
+                    }
+                    val = __builtin_bit_cast(u32x4, o);
+                }
+                out.store(oc0 + wr * 64, oc0 + wr * 64 + 64, trow, oc, val);
+            }
+        }
+    }
 };
 
 }  // namespace msla

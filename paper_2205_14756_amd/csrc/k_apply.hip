@@ -109,7 +109,7 @@ __global__ __launch_bounds__(WR * WC * 64) void apply_project_kernel(const T* __
                                                             const float* __restrict__ kvscale,
                                                             const T* __restrict__ w_proj, T* __restrict__ out,
                                                             int N, int n_hb, int c_out, int blocks_per_image,
-                                                            int n_rb, float eps) {
+                                                            int n_rb, float eps, const T* __restrict__ res) {
     typedef GemmTile<T, WR, WC> G;
     typedef typename Traits<T>::Frag Frag;
     constexpr int HB = G::BK / 16;   // head-branches per iteration
@@ -204,7 +204,14 @@ __global__ __launch_bounds__(WR * WC * 64) void apply_project_kernel(const T* __
     }
     const long tok0 = (long)b * N + n0;
     G::epilogue(acc, tok0, (long)b * N + N, oc0, c_out, wr, wc,
-                [out, c_out](long tok, int oc, f32x4 v) { store_frag<T>(out + tok * c_out + oc, frag_from_f32<T>(v)); });
+                [out, res, c_out](long tok, int oc, f32x4 v) {
+                    if (res != nullptr) {
+                        const f32x4 r = frag_to_f32<T>(load_frag<T>(res + tok * c_out + oc));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += r[e];
+                    }
+                    store_frag<T>(out + tok * c_out + oc, frag_from_f32<T>(v));
+                });
 }
 
 // ------------------------------------------- att fused into projection, weight-stationary
@@ -251,14 +258,15 @@ struct WsApply {
 
 __device__ __forceinline__ int lds_swizzle(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-template <class T, int KCH, int IO>
+template <class T, int KCH, int IO, bool kRes>
 __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restrict__ q_ms,
                                                                const char* __restrict__ kvfrag,
                                                                const float* __restrict__ kvscale,
                                                                const T* __restrict__ w_proj, T* __restrict__ out,
                                                                int N, int n_hb, int c_out, int n_cg,
                                                                int tiles_per_image, long n_tt,
-                                                               long tiles_per_block, float eps) {
+                                                               long tiles_per_block, float eps,
+                                                               const T* __restrict__ res) {
     typedef WsApply<T, KCH, IO> S;
     typedef Traits<T> Tr;
     typedef typename Tr::Vec Vec;
@@ -470,11 +478,24 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     Frag pend[IO][S::JT];
     BufRsrc ores;
     const unsigned out_row = (unsigned)c_out * 2u;
-    auto finish = [&]() {
+    // (kRes: out = res + ..., the residual joining the fp32 sums before their one rounding --
+    // the block's y = x + MSLA(x); o is the origin of the tile the accumulators belong to)
+    auto finish = [&](Origin o) {
 #pragma unroll
         for (int io = 0; io < IO; ++io)
 #pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
+            for (int jt = 0; jt < S::JT; ++jt) {
+                f32x4 v = acc[io][jt];
+                if constexpr (kRes) {
+                    const int row = jt * 16 + x16, oc = ch0 + io * 16 + q * 4;
+                    if (row < N - o.n0 && oc < c_out) {
+                        const f32x4 r = frag_to_f32<T>(load_frag<T>(res + ((size_t)o.tok + row) * (unsigned)c_out + oc));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += r[e];
+                    }
+                }
+                pend[io][jt] = frag_from_f32<T>(v);
+            }
     };
     auto aim_out = [&](Origin o, bool live) {
         const int rows = live ? (N - o.n0 < S::TB ? N - o.n0 : S::TB) : 0;
@@ -563,8 +584,8 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
                 if constexpr (kPieces > 1 && kk == 3 * KCH / 4) flush(1);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            finish();
             if (t > 0) o_out = advance(o_out);
+            finish(o_out);
             o_att = advance(o_att);
             __syncthreads();
         }
@@ -603,7 +624,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 #pragma unroll
                     for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], lo[jt]);
             }
-            finish();
+            finish(o);
             o = advance(o);
         }
         flush_all(o_out);
@@ -612,7 +633,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
 
 template <class T, int KCH, int IO>
 hipError_t run_apply_project_ws(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
-                                void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
+                                void* out, const void* res, long n_tokens, int N, int n_hb, int c_out, float eps,
                                 hipStream_t stream) {
     typedef WsApply<T, KCH, IO> S;
     const int n_cg = (c_out + S::kChanBlock - 1) / S::kChanBlock;
@@ -624,11 +645,20 @@ hipError_t run_apply_project_ws(const void* q_ms, const void* kvfrag, const floa
     const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
     const long tiles_per_block = (n_tt + groups - 1) / groups;
     const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
-    const hipError_t e = allow_dynamic_lds<apply_project_ws_kernel<T, KCH, IO>>(S::kLds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((apply_project_ws_kernel<T, KCH, IO>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
-                       stream, (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb,
-                       c_out, n_cg, tiles_per_image, n_tt, tiles_per_block, eps);
+    // (the residual path is compiled apart: the headline variant has no register to spare for it)
+    if (res != nullptr) {
+        const hipError_t e = allow_dynamic_lds<apply_project_ws_kernel<T, KCH, IO, true>>(S::kLds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((apply_project_ws_kernel<T, KCH, IO, true>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
+                           stream, (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb,
+                           c_out, n_cg, tiles_per_image, n_tt, tiles_per_block, eps, (const T*)res);
+    } else {
+        const hipError_t e = allow_dynamic_lds<apply_project_ws_kernel<T, KCH, IO, false>>(S::kLds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((apply_project_ws_kernel<T, KCH, IO, false>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
+                           stream, (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb,
+                           c_out, n_cg, tiles_per_image, n_tt, tiles_per_block, eps, (const T*)res);
+    }
     return hipGetLastError();
 }
 
@@ -646,7 +676,7 @@ hipError_t run_apply(const void* q_ms, const void* kvfrag, const float* kvscale,
 
 template <class T, int WR, int WC>
 hipError_t run_apply_project_tiled(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
-                                   void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
+                                   void* out, const void* res, long n_tokens, int N, int n_hb, int c_out, float eps,
                                    hipStream_t stream) {
     typedef GemmTile<T, WR, WC> G;
     const int bpi = (N + G::BC - 1) / G::BC;
@@ -660,13 +690,13 @@ hipError_t run_apply_project_tiled(const void* q_ms, const void* kvfrag, const f
     }
     hipLaunchKernelGGL((apply_project_kernel<T, WR, WC>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream,
                        (const T*)q_ms, (const char*)kvfrag, kvscale, (const T*)w_proj, (T*)out, N, n_hb, c_out,
-                       bpi, n_rb, eps);
+                       bpi, n_rb, eps, (const T*)res);
     return hipGetLastError();
 }
 
 template <class T>
 hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* kvscale, const void* w_proj,
-                             void* out, long n_tokens, int N, int n_hb, int c_out, float eps,
+                             void* out, const void* res, long n_tokens, int N, int n_hb, int c_out, float eps,
                              hipStream_t stream) {
 #ifndef MSLA_APPLY_NO_WS
     if constexpr (sizeof(T) == 2) {
@@ -674,13 +704,13 @@ hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* 
         if (n_hb <= 32) {
             const bool narrow = c_out <= 128;
             if (n_hb <= 16)
-                return narrow ? run_apply_project_ws<T, 8, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
-                              : run_apply_project_ws<T, 8, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+                return narrow ? run_apply_project_ws<T, 8, 1>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream)
+                              : run_apply_project_ws<T, 8, 2>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream);
             if (n_hb <= 24)
-                return narrow ? run_apply_project_ws<T, 12, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
-                              : run_apply_project_ws<T, 12, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
-            return narrow ? run_apply_project_ws<T, 16, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream)
-                          : run_apply_project_ws<T, 16, 2>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+                return narrow ? run_apply_project_ws<T, 12, 1>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream)
+                              : run_apply_project_ws<T, 12, 2>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream);
+            return narrow ? run_apply_project_ws<T, 16, 1>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream)
+                          : run_apply_project_ws<T, 16, 2>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream);
         }
     }
 #endif
@@ -690,8 +720,8 @@ hipError_t run_apply_project(const void* q_ms, const void* kvfrag, const float* 
     const long blocks = (n_tokens / N) * ((N + 64 * MSLA_APPLY_WC - 1) / (64 * MSLA_APPLY_WC)) *
                         ((c_out + 64 * MSLA_APPLY_WR - 1) / (64 * MSLA_APPLY_WR));
     if (MSLA_APPLY_WC == 2 && blocks < compute_units())
-        return run_apply_project_tiled<T, MSLA_APPLY_WR, 1>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
-    return run_apply_project_tiled<T, MSLA_APPLY_WR, MSLA_APPLY_WC>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, N, n_hb, c_out, eps, stream);
+        return run_apply_project_tiled<T, MSLA_APPLY_WR, 1>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream);
+    return run_apply_project_tiled<T, MSLA_APPLY_WR, MSLA_APPLY_WC>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, N, n_hb, c_out, eps, stream);
 }
 
 }  // namespace
@@ -707,16 +737,16 @@ hipError_t launch_apply(int dt, const void* q_ms, const void* kvfrag, const floa
 }
 
 hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
-                                const void* w_proj, void* out, long n_tokens, int tokens_per_image, int n_hb,
-                                int c_out, float eps, hipStream_t stream) {
+                                const void* w_proj, void* out, const void* res, long n_tokens, int tokens_per_image,
+                                int n_hb, int c_out, float eps, hipStream_t stream) {
     // more head-branches than the register-resident form holds: the long-contraction kernel
     if (n_hb > 32 && small_product(dt, n_tokens, n_hb * 16, c_out))
-        return launch_small_apply_project(dt, q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out,
+        return launch_small_apply_project(dt, q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, tokens_per_image, n_hb, c_out,
                                           eps, stream);
     switch (dt) {
-        case 0: return run_apply_project<float>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
-        case 1: return run_apply_project<_Float16>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
-        case 2: return run_apply_project<__bf16>(q_ms, kvfrag, kvscale, w_proj, out, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
+        case 0: return run_apply_project<float>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
+        case 1: return run_apply_project<_Float16>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
+        case 2: return run_apply_project<__bf16>(q_ms, kvfrag, kvscale, w_proj, out, res, n_tokens, tokens_per_image, n_hb, c_out, eps, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -1,16 +1,15 @@
 // The FFN+DWConv half of the EfficientViT building block (Section 3.1: a depthwise convolution is
-// inserted into the FFN layer that follows the attention module; Fig. 2 left) and the residual
-// additions of the block.  Declared reading (the paper prints no more than the sentence above):
+// inserted into the FFN layer that follows the attention module; Fig. 2 left).  Declared reading (the paper prints no more than the sentence above):
 //   h   = act(W1 y)                      1x1 expand, C -> E
 //   g   = act(DW3x3(h))                  depthwise 3x3, stride 1, zero padding 1, cross-correlation
 //   out = y + W2 g                       1x1 project, E -> C, no activation, residual
 // with act = ReLU or hard-swish, no bias, no normalisation.
 //
-// Kernels here: the depthwise pass (vector ALUs, both activations fused: it reads the expand
-// projection's result before its activation), the projection E -> C with the residual added to
-// the fp32 sums before their one rounding, and a plain residual addition (y = x + MSLA(x)).
-// The expand projection is the library's ordinary 1x1 projection.
-#include "gemm_tile.h"
+// Kernel here: the depthwise pass with its activation (vector ALUs).  Both projections are the
+// library's 1x1 projection kernels: the first applies the activation to its fp32 sums, the second adds
+// the residual to them, each before the one rounding; the block's y = x + MSLA(x) is formed the same
+// way, in the epilogue of the attention module's output projection.
+#include "msla_device.h"
 #include "msla_kernels.h"
 
 namespace msla {
@@ -50,10 +49,12 @@ struct Pack {
     }
 };
 
-constexpr int kDwRows = 8;       // output rows per thread (its window slides down them)
+constexpr int kDwRows = 16;      // output rows per thread (its window slides down them)
 
-// g = act(DW3x3(act(h))).  A thread owns 16 bytes of channels at one column x and slides a 3x3
-// window down kDwRows rows: three 16-byte loads per new row, the filter taps in registers.
+// g = act(DW3x3(h)), h being the expand projection's ACTIVATED result (its kernel applies the
+// activation to its fp32 sums).  A thread owns 16 bytes of channels at one column x and slides a 3x3
+// window down kDwRows rows: three 16-byte loads per new row -- requested one row ahead of their
+// use, so a row's arithmetic covers the next row's latency -- and the filter taps in registers.
 // Consecutive threads take consecutive channel vectors, so every load and store is contiguous
 // across the wave; the neighbouring columns' reads of the same rows hit the caches.
 template <class T, int ACT>
@@ -81,25 +82,39 @@ __global__ __launch_bounds__(256) void ffn_dw_kernel(const T* __restrict__ h, co
     const T* img = h + (long)b * H * W * E + c0;
     T* out = g + (long)b * H * W * E + c0;
     float win[3][3][V];        // [row slot][column x-1, x, x+1][channel]
-    auto load_row = [&](int yy, float (&row)[3][V]) {
+    struct Raw {
+        u32x4 v[3];
+        bool ok[3];
+    };
+    auto request = [&](int yy, Raw& r) {
 #pragma unroll
         for (int dx = 0; dx < 3; ++dx) {
             const int xx = x + dx - 1;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-            if (ok) v = *(const u32x4*)(img + ((long)yy * W + xx) * E);
-            float f[V];
-            Pack<T>::unpack(v, f);
-#pragma unroll
-            for (int j = 0; j < V; ++j) row[dx][j] = ok ? activate<ACT>(f[j]) : 0.f;     // padding is zero AFTER the activation
+            r.ok[dx] = yy >= 0 && yy < H && xx >= 0 && xx < W;
+            r.v[dx] = u32x4{0u, 0u, 0u, 0u};
+            if (r.ok[dx]) r.v[dx] = *(const u32x4*)(img + ((long)yy * W + xx) * E);
         }
     };
-    load_row(y0 - 1, win[0]);
-    load_row(y0, win[1]);
+    auto unpack_row = [&](const Raw& r, float (&row)[3][V]) {
+#pragma unroll
+        for (int dx = 0; dx < 3; ++dx) {
+            float f[V];
+            Pack<T>::unpack(r.v[dx], f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) row[dx][j] = f[j];        // (a masked load is zero: the padding)
+        }
+    };
+    Raw ahead;
+    request(y0 - 1, ahead);
+    unpack_row(ahead, win[0]);
+    request(y0, ahead);
+    unpack_row(ahead, win[1]);
+    request(y0 + 1, ahead);
 #pragma unroll
     for (int r = 0; r < kDwRows; ++r) {
         const int yy = y0 + r;
-        load_row(yy + 1, win[(r + 2) % 3]);
+        unpack_row(ahead, win[(r + 2) % 3]);           // row yy + 1
+        if (r + 1 < kDwRows) request(yy + 2, ahead);   // in flight during this row's arithmetic
         if (yy < H) {
             float acc[V];
 #pragma unroll
@@ -117,61 +132,6 @@ __global__ __launch_bounds__(256) void ffn_dw_kernel(const T* __restrict__ h, co
     }
 }
 
-// y = a + b, 16 bytes a thread, fp32 addition, one rounding.
-template <class T>
-__global__ __launch_bounds__(256) void residual_add_kernel(const T* __restrict__ a, const T* __restrict__ b,
-                                                           T* __restrict__ y, long n_vec) {
-    constexpr int V = Pack<T>::N;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_vec) return;
-    float fa[V], fb[V];
-    Pack<T>::unpack(((const u32x4*)a)[i], fa);
-    Pack<T>::unpack(((const u32x4*)b)[i], fb);
-#pragma unroll
-    for (int j = 0; j < V; ++j) fa[j] += fb[j];
-    ((u32x4*)y)[i] = Pack<T>::pack(fa);
-}
-
-// out[n, c] = res[n, c] + sum_e g[n, e] * w2[c, e]: tiled (256 channels x 128 tokens per workgroup,
-// 64 x 64 per wave, any contraction length), next slab's loads in flight during the matrix
-// instructions; the residual joins the fp32 sums in the epilogue.
-template <class T, int WR, int WC>
-__global__ __launch_bounds__(WR * WC * 64) void ffn_project_kernel(const T* __restrict__ g, const T* __restrict__ w2,
-                                                                   const T* __restrict__ res, T* __restrict__ out,
-                                                                   long n_tokens, int E, int c_out, int n_rb) {
-    typedef GemmTile<T, WR, WC> G;
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* ldsR = lds;
-    char* ldsC = lds + G::kLdsR;
-    const unsigned L = xcd_remap(blockIdx.x, gridDim.x);
-    const int rb = L % n_rb;
-    const long tok0 = (long)(L / n_rb) * G::BC;
-    const int oc0 = rb * G::BR;
-    const int wave = threadIdx.x >> 6;
-    const int wr = wave % WR, wc = wave / WR;
-
-    f32x4 acc[4][4];
-    G::zero(acc);
-    u32x4 rw[G::kVecR], rc[G::kVecC];
-    G::load_global(rw, w2, oc0, c_out, E, 0, E);
-    G::load_global(rc, g, tok0, n_tokens, E, 0, E);
-    for (int k0 = 0; k0 < E; k0 += G::BK) {
-        G::store_lds_r(ldsR, rw);
-        G::store_lds_c(ldsC, rc);
-        __syncthreads();
-        if (k0 + G::BK < E) {
-            G::load_global(rw, w2, oc0, c_out, E, k0 + G::BK, E);
-            G::load_global(rc, g, tok0, n_tokens, E, k0 + G::BK, E);
-        }
-        G::mma(acc, ldsR, ldsC, wr, wc);
-        __syncthreads();
-    }
-    G::epilogue(acc, tok0, n_tokens, oc0, c_out, wr, wc, [res, out, c_out](long tok, int oc, f32x4 v) {
-        const f32x4 r = frag_to_f32<T>(load_frag<T>(res + tok * c_out + oc));
-        store_frag<T>(out + tok * c_out + oc, frag_from_f32<T>(f32x4{v[0] + r[0], v[1] + r[1], v[2] + r[2], v[3] + r[3]}));
-    });
-}
-
 template <class T>
 hipError_t run_dw(const void* h, const void* w_dw, void* g, int B, int H, int W, int E, int act, hipStream_t stream) {
     const long n_items = (long)B * ((H + kDwRows - 1) / kDwRows) * W * (E / Pack<T>::N);
@@ -184,30 +144,6 @@ hipError_t run_dw(const void* h, const void* w_dw, void* g, int B, int H, int W,
     return hipGetLastError();
 }
 
-template <class T>
-hipError_t run_add(const void* a, const void* b, void* y, long n_elems, hipStream_t stream) {
-    const long n_vec = n_elems / Pack<T>::N;
-    const long nblocks = (n_vec + 255) / 256;
-    if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((residual_add_kernel<T>), dim3((unsigned)nblocks), dim3(256), 0, stream, (const T*)a, (const T*)b, (T*)y, n_vec);
-    return hipGetLastError();
-}
-
-template <class T>
-hipError_t run_ffn_project(const void* g, const void* w2, const void* res, void* out, long n_tokens, int E, int c_out,
-                           hipStream_t stream) {
-    typedef GemmTile<T, 4, 2> G;
-    const int n_rb = (c_out + G::BR - 1) / G::BR;
-    const long nblocks = ((n_tokens + G::BC - 1) / G::BC) * n_rb;
-    if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    constexpr int kLds = G::kLdsR + G::kLdsC;
-    const hipError_t e = allow_dynamic_lds<ffn_project_kernel<T, 4, 2>>(kLds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ffn_project_kernel<T, 4, 2>), dim3((unsigned)nblocks), dim3(G::kThreads), kLds, stream, (const T*)g,
-                       (const T*)w2, (const T*)res, (T*)out, n_tokens, E, c_out, n_rb);
-    return hipGetLastError();
-}
-
 }  // namespace
 
 hipError_t launch_ffn_dw(int dt, const void* h, const void* w_dw, void* g, int B, int H, int W, int E, int act,
@@ -216,25 +152,6 @@ hipError_t launch_ffn_dw(int dt, const void* h, const void* w_dw, void* g, int B
         case 0: return run_dw<float>(h, w_dw, g, B, H, W, E, act, stream);
         case 1: return run_dw<_Float16>(h, w_dw, g, B, H, W, E, act, stream);
         case 2: return run_dw<__bf16>(h, w_dw, g, B, H, W, E, act, stream);
-    }
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_residual_add(int dt, const void* a, const void* b, void* y, long n_elems, hipStream_t stream) {
-    switch (dt) {
-        case 0: return run_add<float>(a, b, y, n_elems, stream);
-        case 1: return run_add<_Float16>(a, b, y, n_elems, stream);
-        case 2: return run_add<__bf16>(a, b, y, n_elems, stream);
-    }
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_ffn_project(int dt, const void* g, const void* w2, const void* res, void* out, long n_tokens, int E,
-                              int c_out, hipStream_t stream) {
-    switch (dt) {
-        case 0: return run_ffn_project<float>(g, w2, res, out, n_tokens, E, c_out, stream);
-        case 1: return run_ffn_project<_Float16>(g, w2, res, out, n_tokens, E, c_out, stream);
-        case 2: return run_ffn_project<__bf16>(g, w2, res, out, n_tokens, E, c_out, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -35,6 +35,29 @@ struct PlainDest {
     T* y;
     long n_tokens;
     int c_out;
+    // optional residual [n_tokens, c_out] that the tiled kernel adds to the fp32 sums before their one
+    // rounding (y = res + x w^T); nullptr: none
+    const T* res = nullptr;
+    // optional activation applied to the fp32 sums before their one rounding: -1 none, 0 ReLU,
+    // 1 hard-swish a * clip(a + 3, 0, 6) / 6 (the FFN's expand projection)
+    int act = -1;
+    __host__ __device__ __forceinline__ bool has_residual() const { return res != nullptr; }
+    // 16 bytes of the residual at (token, channel), zero past the ends
+    __device__ __forceinline__ u32x4 residual16(long tok, int oc) const {
+        u32x4 r = {0u, 0u, 0u, 0u};
+        if (tok < n_tokens && oc < c_out) r = *(const u32x4*)(res + tok * c_out + oc);
+        return r;
+    }
+    __device__ __forceinline__ f32x4 activate(f32x4 v) const {
+        if (act == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+        } else if (act == 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = v[e] * fminf(fmaxf(v[e] + 3.f, 0.f), 6.f) * (1.0f / 6.0f);
+        }
+        return v;
+    }
     struct Tile {
         BufRsrc y;
         unsigned row_bytes;
@@ -77,6 +100,9 @@ struct PlainDest {
 // a head-major map must stay below 2^31 bytes (32-bit offsets inside a tile's resource).
 template <class T>
 struct QkvSplitDest {
+    __host__ __device__ __forceinline__ bool has_residual() const { return false; }
+    __device__ __forceinline__ u32x4 residual16(long, int) const { return u32x4{0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ f32x4 activate(f32x4 v) const { return v; }
     T* q_ms;
     long q_ms_stride;
     T* kv_raw;
@@ -140,6 +166,9 @@ struct QkvSplitDest {
 // goes to is known when the kernel is compiled: no branches, one offset a lane.
 template <class T>
 struct QkvHeadDest {
+    __host__ __device__ __forceinline__ bool has_residual() const { return false; }
+    __device__ __forceinline__ u32x4 residual16(long, int) const { return u32x4{0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ f32x4 activate(f32x4 v) const { return v; }
     T* q_ms;
     long q_ms_stride;
     T* kv_raw;
@@ -303,7 +332,19 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
         if (++slab == slabs) {
             // every wave finished reading the buffer just consumed before the barrier above, and it is
             // not refilled before the next step: stage the results there
-            G::epilogue_lds(acc, here, rb * G::BR, wr, wc, ep.tile(cb * G::BC));
+            {
+#pragma unroll
+                for (int io = 0; io < 4; ++io)
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) acc[io][jt] = ep.activate(acc[io][jt]);
+            }
+            if (ep.has_residual()) {
+                const long tok0 = (long)cb * G::BC;
+                G::epilogue_lds_residual(acc, here, rb * G::BR, wr, wc, ep.tile(tok0),
+                                         [&](int row, int oc) { return ep.residual16(tok0 + row, oc); });
+            } else {
+                G::epilogue_lds(acc, here, rb * G::BR, wr, wc, ep.tile(cb * G::BC));
+            }
             G::zero(acc);
             slab = 0;
             --left;
@@ -526,7 +567,7 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
 #pragma unroll
         for (int io = 0; io < S::IO; ++io)
 #pragma unroll
-            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(acc[io][jt]);
+            for (int jt = 0; jt < S::JT; ++jt) pend[io][jt] = frag_from_f32<T>(ep.activate(acc[io][jt]));
         dest = ep.tile(tile * S::TB);
         __syncthreads();
         cur ^= 1;
@@ -565,8 +606,10 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
     if constexpr (sizeof(T) == 2) {
         // short contraction: weights stay in registers
 #ifndef MSLA_PROJ_NO_WS
-        if (c_in <= 128) return run_project_ws<T, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
-        if (c_in <= 256) return run_project_ws<T, 8, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+        if (!ep.has_residual()) {      // (the weight-stationary form has no residual path)
+            if (c_in <= 128) return run_project_ws<T, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+            if (c_in <= 256) return run_project_ws<T, 8, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+        }
 #endif
     }
     typedef ProjTile<T> G;
@@ -598,6 +641,28 @@ hipError_t launch_linear(int dt, const void* x, const void* w, void* y, long n_t
         case 0: return run_project<float>(x, w, n_tokens, c_in, c_out, PlainDest<float>{(float*)y, n_tokens, c_out}, stream);
         case 1: return run_project<_Float16>(x, w, n_tokens, c_in, c_out, PlainDest<_Float16>{(_Float16*)y, n_tokens, c_out}, stream);
         case 2: return run_project<__bf16>(x, w, n_tokens, c_in, c_out, PlainDest<__bf16>{(__bf16*)y, n_tokens, c_out}, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+// y = act(x w^T) (the FFN's expand projection: act 0 ReLU, 1 hard-swish)
+hipError_t launch_linear_act(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out, int act,
+                             hipStream_t stream) {
+    switch (dt) {
+        case 0: return run_project<float>(x, w, n_tokens, c_in, c_out, PlainDest<float>{(float*)y, n_tokens, c_out, nullptr, act}, stream);
+        case 1: return run_project<_Float16>(x, w, n_tokens, c_in, c_out, PlainDest<_Float16>{(_Float16*)y, n_tokens, c_out, nullptr, act}, stream);
+        case 2: return run_project<__bf16>(x, w, n_tokens, c_in, c_out, PlainDest<__bf16>{(__bf16*)y, n_tokens, c_out, nullptr, act}, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+// y = res + x w^T (the FFN's hidden -> C projection with the block's residual: Section 3.1, Fig. 2 left)
+hipError_t launch_linear_residual(int dt, const void* x, const void* w, const void* res, void* y, long n_tokens,
+                                  int c_in, int c_out, hipStream_t stream) {
+    switch (dt) {
+        case 0: return run_project<float>(x, w, n_tokens, c_in, c_out, PlainDest<float>{(float*)y, n_tokens, c_out, (const float*)res}, stream);
+        case 1: return run_project<_Float16>(x, w, n_tokens, c_in, c_out, PlainDest<_Float16>{(_Float16*)y, n_tokens, c_out, (const _Float16*)res}, stream);
+        case 2: return run_project<__bf16>(x, w, n_tokens, c_in, c_out, PlainDest<__bf16>{(__bf16*)y, n_tokens, c_out, (const __bf16*)res}, stream);
     }
     return hipErrorInvalidValue;
 }

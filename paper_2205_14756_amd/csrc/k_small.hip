@@ -33,7 +33,16 @@ template <class T>
 struct SmallPlain {
     T* y;
     int c_out;
+    const T* res = nullptr;       // optional residual [n_tokens, c_out], added to the fp32 sums
     __device__ __forceinline__ T* at(long tok, int g) const { return y + tok * c_out + g * 16; }
+    __device__ __forceinline__ f32x4 plus_residual(f32x4 v, long tok, int g, int c) const {
+        if (res != nullptr) {
+            const f32x4 r = frag_to_f32<T>(load_frag<T>(res + tok * c_out + g * 16 + c));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += r[e];
+        }
+        return v;
+    }
 };
 // ... for the Q/K/V projection: group g = h*3 + t; Q goes to the branch-0 columns of the
 // multi-scale Q map, K and V to the K|V map (token and head strides in elements)
@@ -43,6 +52,7 @@ struct SmallQkv {
     long q_ms_stride;
     T* kv_raw;
     long kv_tok_stride, kv_head_stride;
+    __device__ __forceinline__ f32x4 plus_residual(f32x4 v, long, int, int) const { return v; }
     __device__ __forceinline__ T* at(long tok, int g) const {
         const int h = g / 3, t = g - 3 * h;
         return t == 0 ? q_ms + tok * q_ms_stride + h * 16
@@ -215,7 +225,9 @@ __global__ __launch_bounds__(kSmallThreads) void small_project_kernel(const T* _
 #pragma unroll
             for (int jt = 0; jt < 2; ++jt) {
                 const int row = jt * 16 + x16;
-                if (row < rows) store_frag<T>(dest.at(tok0 + row, ch0 >> 4) + q * 4, frag_from_f32<T>(acc[jt]));
+                if (row < rows)
+                    store_frag<T>(dest.at(tok0 + row, ch0 >> 4) + q * 4,
+                                  frag_from_f32<T>(dest.plus_residual(acc[jt], tok0 + row, ch0 >> 4, q * 4)));
             }
         }
         __syncthreads();       // the tile is rewritten by the next iteration
@@ -277,16 +289,16 @@ hipError_t launch_small_qkv_project(int dt, const void* x, const void* w_qkv, vo
 }
 
 hipError_t launch_small_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
-                                      const void* w_proj, void* out, long n_tokens, int tokens_per_image, int n_hb,
-                                      int c_out, float eps, hipStream_t stream) {
+                                      const void* w_proj, void* out, const void* res, long n_tokens, int tokens_per_image,
+                                      int n_hb, int c_out, float eps, hipStream_t stream) {
     const int N = tokens_per_image;
     const int tpi = (N + kSmallTB - 1) / kSmallTB;
     const long n_tiles = (n_tokens / N) * tpi;
     const SmallAttArgs aa = {(const char*)kvfrag, kvscale, N, n_hb, eps};
     const int K = n_hb * 16;
     switch (dt) {
-        case 1: return run_small_k<_Float16, true>(q_ms, w_proj, SmallPlain<_Float16>{(_Float16*)out, c_out}, aa, n_tokens, K, c_out, n_tiles, tpi, stream);
-        case 2: return run_small_k<__bf16, true>(q_ms, w_proj, SmallPlain<__bf16>{(__bf16*)out, c_out}, aa, n_tokens, K, c_out, n_tiles, tpi, stream);
+        case 1: return run_small_k<_Float16, true>(q_ms, w_proj, SmallPlain<_Float16>{(_Float16*)out, c_out, (const _Float16*)res}, aa, n_tokens, K, c_out, n_tiles, tpi, stream);
+        case 2: return run_small_k<__bf16, true>(q_ms, w_proj, SmallPlain<__bf16>{(__bf16*)out, c_out, (const __bf16*)res}, aa, n_tokens, K, c_out, n_tiles, tpi, stream);
     }
     return hipErrorNotSupported;
 }

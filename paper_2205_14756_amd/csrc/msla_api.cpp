@@ -219,7 +219,7 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
                                 const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B,
                                 int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
                                 float eps, msla_dtype dt, msla_layout layout, void* stream,
-                                void* const* events, unsigned options) {
+                                void* const* events, unsigned options, const void* residual = nullptr) {
     if (!x || !w_qkv || !w_proj || !out || !workspace || C <= 0) return MSLA_ERR_INVALID_ARG;
     if (options & ~(MSLA_OPT_GENERAL_AGGREGATION | MSLA_OPT_STATE_VALU | kStageBits)) return MSLA_ERR_INVALID_ARG;
     if ((options & kStageBits) && layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
@@ -277,7 +277,7 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     // normalise-and-apply fused with the output projection
     if (stage_wanted(options, MSLA_OPT_STAGE_APPLY) &&
         msla::launch_apply_project((int)dt, q_ms, ws + wo.kvfrag, reinterpret_cast<float*>(ws + wo.kvscale),
-                                   w_proj, out_tok, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
+                                   w_proj, out_tok, residual, s.T, (int)s.N, s.S * s.heads, C, eps, hs) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     if (layout == MSLA_NCHW &&
         msla::launch_transpose((int)dt, out_tok, out, s.B, (int)s.N, C, hs) != hipSuccess)
@@ -407,9 +407,9 @@ msla_status msla_ffn_forward(const void* y, const void* w1, const void* w_dw, co
     hipStream_t hs = static_cast<hipStream_t>(stream);
     char* h_pre = static_cast<char*>(workspace);
     char* g = h_pre + align_up((size_t)T * hidden * elem_size(dt));
-    if (msla::launch_linear((int)dt, y, w1, h_pre, T, C, hidden, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_linear_act((int)dt, y, w1, h_pre, T, C, hidden, (int)act, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
     if (msla::launch_ffn_dw((int)dt, h_pre, w_dw, g, B, H, W, hidden, (int)act, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
-    if (msla::launch_ffn_project((int)dt, g, w2, y, out, T, hidden, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_linear_residual((int)dt, g, w2, y, out, T, hidden, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
     return MSLA_OK;
 }
 
@@ -440,12 +440,10 @@ msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_d
     const size_t y_bytes = align_up((size_t)B * H * W * C * elem_size(dt));
     char* ybuf = static_cast<char*>(workspace);
     char* rest = ybuf + y_bytes;
-    // MSLA(x) lands in `out`, which is free until the FFN's last kernel writes the block's result there
-    msla_status st = forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, out, rest, workspace_bytes - y_bytes, B, C, H, W, heads,
-                                  head_dim, scales, n_scales, eps, dt, MSLA_NHWC, stream, nullptr, 0u);
+    // y = x + MSLA(x) in one rounding: x joins the output projection's fp32 sums as a residual
+    const msla_status st = forward_impl(x, w_qkv, w_dw, w_gpw, w_proj, ybuf, rest, workspace_bytes - y_bytes, B, C, H, W,
+                                        heads, head_dim, scales, n_scales, eps, dt, MSLA_NHWC, stream, nullptr, 0u, x);
     if (st != MSLA_OK) return st;
-    if (msla::launch_residual_add((int)dt, x, out, ybuf, (long)B * H * W * C, static_cast<hipStream_t>(stream)) != hipSuccess)
-        return MSLA_ERR_LAUNCH;
     return msla_ffn_forward(ybuf, w1, w_ffn_dw, w2, out, rest, workspace_bytes - y_bytes, B, C, H, W, hidden, act, dt, stream);
 }
 

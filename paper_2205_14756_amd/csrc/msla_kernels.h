@@ -63,9 +63,10 @@ hipError_t launch_state_finalize(int dt, const float* partials, float* kv32, voi
 hipError_t launch_apply(int dt, const void* q_ms, const void* kvfrag, const float* kvscale, void* att,
                         long n_tokens, int tokens_per_image, int n_hb, float eps, hipStream_t stream);
 
-// out[n, c] = sum_m att[n, m] * w_proj[c, m] with att produced on the fly
+// out[n, c] = (res ? res[n, c] : 0) + sum_m att[n, m] * w_proj[c, m] with att produced on the fly; the optional
+// residual [n_tokens, c_out] joins the fp32 sums before their one rounding
 hipError_t launch_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
-                                const void* w_proj, void* out, long n_tokens, int tokens_per_image,
+                                const void* w_proj, void* out, const void* res, long n_tokens, int tokens_per_image,
                                 int n_hb, int c_out, float eps, hipStream_t stream);
 
 // The same three operations for 16-bit storage types with a contraction of 257 .. 1024 slots and
@@ -77,22 +78,23 @@ hipError_t launch_small_qkv_project(int dt, const void* x, const void* w_qkv, vo
                                     void* kv_raw, long kv_tok_stride, long kv_head_stride, long n_tokens, int c_in,
                                     int heads, hipStream_t stream);
 hipError_t launch_small_apply_project(int dt, const void* q_ms, const void* kvfrag, const float* kvscale,
-                                      const void* w_proj, void* out, long n_tokens, int tokens_per_image, int n_hb,
-                                      int c_out, float eps, hipStream_t stream);
+                                      const void* w_proj, void* out, const void* res, long n_tokens, int tokens_per_image,
+                                      int n_hb, int c_out, float eps, hipStream_t stream);
 // whether a [n_tokens x K] by [K x c_out] product is "small" in that sense
 inline bool small_product(int dt, long n_tokens, int K, int c_out) {
     return dt != 0 && K > 256 && K <= 1024 && ((n_tokens + 31) / 32) * ((c_out + 127) / 128) <= 8L * compute_units();
 }
 
 // The FFN+DWConv half of the building block (k_ffn.hip).  act: 0 ReLU, 1 hard-swish.
-//   g[b,y,x,c] = act(sum_{u,v} w_dw[c,u,v] * act(h[b, y+u-1, x+v-1, c]))     (zero outside the map)
+//   g[b,y,x,c] = act(sum_{u,v} w_dw[c,u,v] * h[b, y+u-1, x+v-1, c])     (zero outside the map)
 hipError_t launch_ffn_dw(int dt, const void* h, const void* w_dw, void* g, int B, int H, int W, int E, int act,
                          hipStream_t stream);
-//   y = a + b (n_elems a multiple of 8)
-hipError_t launch_residual_add(int dt, const void* a, const void* b, void* y, long n_elems, hipStream_t stream);
-//   out[n, c] = res[n, c] + sum_e g[n, e] * w2[c, e]
-hipError_t launch_ffn_project(int dt, const void* g, const void* w2, const void* res, void* out, long n_tokens, int E,
-                              int c_out, hipStream_t stream);
+//   y[n, o] = act(sum_c x[n, c] * w[o, c])   (k_project.hip; the activation is applied to the fp32 sums)
+hipError_t launch_linear_act(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out, int act,
+                             hipStream_t stream);
+//   y[n, o] = res[n, o] + sum_c x[n, c] * w[o, c]   (k_project.hip, tiled form; the residual joins the fp32 sums)
+hipError_t launch_linear_residual(int dt, const void* x, const void* w, const void* res, void* y, long n_tokens,
+                                  int c_in, int c_out, hipStream_t stream);
 
 // Softmax attention per image and head on qkv [B, N, 3*heads*16] -> att [B, N, heads*16] (k_softmax.hip)
 hipError_t launch_softmax_attention(int dt, const void* qkv, void* att, int B, int N, int heads, hipStream_t stream);
