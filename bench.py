@@ -377,6 +377,24 @@ def main():
                 "frac_on_fused_bytes": round(fused_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "frac_on_bytes_as_built": round(built_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del w1, wfd, w2, bws, bout
+        # the backward pass of ReLU linear attention (gradient of Eq. (3)) on the headline shape: three passes
+        # over the tokens (forward state: K, V; dS: Q, dAtt; gradients: Q, K, V, dAtt in, dQ, dK, dV out) =
+        # 11 units of e*Ct*T
+        bq = torch.randn((wl.B, wl.H * wl.W, 3 * wl.heads * wl.head_dim), device="cuda").to(tdt_of[wl.dtype])
+        bda = torch.randn((wl.B, wl.H * wl.W, wl.heads * wl.head_dim), device="cuda").to(tdt_of[wl.dtype])
+        bdq = torch.empty_like(bq)
+        bws_ = torch.empty(msla.msla_linear_attention_backward_workspace_bytes(wl.B, wl.H * wl.W, wl.heads, wl.head_dim,
+                                                                                tdt_of[wl.dtype]), dtype=torch.uint8, device="cuda")
+        bwd_ = lambda: msla.msla_linear_attention_backward(bq, bda, wl.heads, wl.head_dim, wl.eps, d_qkv=bdq, workspace=bws_,
+                                                           stream=stream)
+        for _ in range(100):
+            bwd_()
+        ms = timed(bwd_, 300)
+        others[wl.name + ":linear_attention_backward"] = {
+            "entry": "msla_linear_attention_backward", "dtype": wl.dtype, "tokens": wl.tokens, "ms_per_module": round(ms, 5),
+            "tokens_per_s": round(wl.tokens / (ms * 1e-3), 1),
+            "frac_on_three_pass_bytes": round(11 * unit / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del bq, bda, bdq, bws_
         # Fig. 3 of the paper restated on this GPU: softmax attention (Eq. (1) with the exponential
         # similarity) against ReLU linear attention (Eq. (3); msla_core_forward without aggregated scales)
         # on the same projected maps, headline batch / heads / type, at three token counts.  The linear

@@ -205,6 +205,22 @@ msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_d
                                const int* scales, int n_scales, float eps,
                                int hidden, msla_act act, msla_dtype dt, void* stream);
 
+/* Backward pass of ReLU linear attention: the gradient of Eq. (3) (Section 3.1) with respect to Q, K and V.
+ * The paper trains its models (Section 4.1) and prints no gradient, so this is the derivative of the
+ * forward definition att_n = relu(Q_n) KV / (relu(Q_n) Ksum + eps), KV|Ksum = sum_n relu(K_n)^T [V_n, 1], per
+ * image and head, the rectifier's derivative taken as 0 at 0:
+ *   qkv   [B, N, 3*heads*head_dim]  the forward input (channel (h*3 + t)*head_dim + e)
+ *   d_att [B, N, heads*head_dim]    dL/d att
+ *   d_qkv [B, N, 3*heads*head_dim]  dL/d qkv (written; same channel order)
+ * fp32 sums, storage type dt; two passes over the tokens around a second head_dim x (head_dim+1) reduction,
+ * summed in a fixed order (reproducible).  head_dim == 16 only.  workspace: the query below (a few KB per state). */
+msla_status msla_linear_attention_backward_workspace_bytes(int B, int N, int heads, int head_dim, msla_dtype dt,
+                                                           size_t* bytes);
+msla_status msla_linear_attention_backward(const void* qkv, const void* d_att, void* d_qkv,
+                                           void* workspace, size_t workspace_bytes,
+                                           int B, int N, int heads, int head_dim, float eps,
+                                           msla_dtype dt, void* stream);
+
 /* Softmax attention, the form the paper's ReLU linear attention replaces (Section 3.1: Eq. (1) with
  * Sim(Q, K) = exp(Q K^T / sqrt(d)); Fig. 3 compares the two): for every image and head
  *     att_i = sum_j exp(Q_i . K_j / sqrt(d)) V_j / sum_j exp(Q_i . K_j / sqrt(d)).

@@ -447,6 +447,45 @@ msla_status msla_block_forward(const void* x, const void* w_qkv, const void* w_d
     return msla_ffn_forward(ybuf, w1, w_ffn_dw, w2, out, rest, workspace_bytes - y_bytes, B, C, H, W, hidden, act, dt, stream);
 }
 
+msla_status msla_linear_attention_backward_workspace_bytes(int B, int N, int heads, int head_dim, msla_dtype dt,
+                                                           size_t* bytes) {
+    if (!bytes) return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    const msla_status st = check_shape(B, 1, N, heads, head_dim, nullptr, 0, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    *bytes = 2 * carve(s, dt, /*with_maps=*/false).total;
+    return MSLA_OK;
+}
+
+msla_status msla_linear_attention_backward(const void* qkv, const void* d_att, void* d_qkv, void* workspace,
+                                           size_t workspace_bytes, int B, int N, int heads, int head_dim, float eps,
+                                           msla_dtype dt, void* stream) {
+    if (!qkv || !d_att || !d_qkv || !workspace) return MSLA_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
+    if (!aligned16(qkv) || !aligned16(d_att) || !aligned16(d_qkv) || !aligned16(workspace)) return MSLA_ERR_INVALID_ARG;
+    Shape s;
+    msla_status st = check_shape(B, 1, N, heads, head_dim, nullptr, 0, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    const Workspace wo = carve(s, dt, /*with_maps=*/false);
+    if (workspace_bytes < 2 * wo.total) return MSLA_ERR_WORKSPACE;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    char* ws2 = ws + wo.total;
+    const size_t e = elem_size(dt);
+    const char* base = static_cast<const char*>(qkv);
+    // forward state S of Eq. (3) (the library's own state kernels), then dS, then the three gradients
+    st = run_state(s, dt, base, 3L * s.Ct, 48, base + 16 * e, 3L * s.Ct, 48, base + 32 * e, 3L * s.Ct, 48, nullptr, nullptr,
+                   ws, wo, nullptr, /*copy_raw_q=*/0, hs);
+    if (st != MSLA_OK) return st;
+    if (msla::launch_linear_attention_backward((int)dt, qkv, d_att, reinterpret_cast<const float*>(ws + wo.kv32),
+                                               reinterpret_cast<float*>(ws2 + wo.partials),
+                                               reinterpret_cast<float*>(ws2 + wo.kv32), ws2 + wo.kvfrag,
+                                               reinterpret_cast<float*>(ws2 + wo.kvscale), d_qkv, B, N, heads, s.nchunks,
+                                               s.tiles_per_chunk, eps, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
 msla_status msla_softmax_attention(const void* qkv, void* att, int B, int N, int heads, int head_dim, msla_dtype dt,
                                    void* stream) {
     if (!qkv || !att || B <= 0 || N <= 0 || heads <= 0 || head_dim <= 0) return MSLA_ERR_INVALID_ARG;

@@ -99,6 +99,14 @@ hipError_t launch_linear_residual(int dt, const void* x, const void* w, const vo
 // Softmax attention per image and head on qkv [B, N, 3*heads*16] -> att [B, N, heads*16] (k_softmax.hip)
 hipError_t launch_softmax_attention(int dt, const void* qkv, void* att, int B, int N, int heads, hipStream_t stream);
 
+// Gradient of Eq. (3) (k_backward.hip): d_qkv [B, N, 3*heads*16] from qkv, d_att [B, N, heads*16] and the forward
+// states kv32 [B*heads, 16, 17]; partials [B*heads*nchunks*272], ds32 [B*heads*272], frag_scratch [B*heads*2048 bytes]
+// and scale_scratch [B*heads] are work buffers.
+hipError_t launch_linear_attention_backward(int dt, const void* qkv, const void* d_att, const float* kv32, float* partials,
+                                            float* ds32, void* frag_scratch, float* scale_scratch, void* d_qkv, int B,
+                                            int N, int heads, int nchunks, int tiles_per_chunk, float eps,
+                                            hipStream_t stream);
+
 // dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);

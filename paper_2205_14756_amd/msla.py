@@ -34,7 +34,8 @@ EXPORTS = ("msla_error_string", "msla_workspace_bytes", "msla_forward", "msla_fo
            "msla_core_forward",
            "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear",
            "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward",
-           "msla_softmax_attention")
+           "msla_softmax_attention", "msla_linear_attention_backward_workspace_bytes",
+           "msla_linear_attention_backward")
 
 MSLA_ACT_RELU, MSLA_ACT_HSWISH = 0, 1
 
@@ -85,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.msla_block_forward.restype = i
     lib.msla_softmax_attention.argtypes = [vp, vp, i, i, i, i, i, vp]
     lib.msla_softmax_attention.restype = i
+    lib.msla_linear_attention_backward_workspace_bytes.argtypes = [i, i, i, i, i, ctypes.POINTER(sz)]
+    lib.msla_linear_attention_backward_workspace_bytes.restype = i
+    lib.msla_linear_attention_backward.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, f, i, vp]
+    lib.msla_linear_attention_backward.restype = i
     lib.msla_linear.argtypes = [vp, vp, vp, ctypes.c_long, i, i, i, vp]
     lib.msla_linear.restype = i
     _lib = lib
@@ -320,3 +325,30 @@ def msla_softmax_attention(qkv, heads, head_dim, att=None, stream=None):
     if st != MSLA_OK:
         raise MslaError(st, "msla_softmax_attention")
     return att
+
+
+def msla_linear_attention_backward_workspace_bytes(B, N, heads, head_dim, dtype) -> int:
+    out = ctypes.c_size_t(0)
+    st = load_library().msla_linear_attention_backward_workspace_bytes(B, N, heads, head_dim, _DTYPES[dtype],
+                                                                       ctypes.byref(out))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_linear_attention_backward_workspace_bytes")
+    return int(out.value)
+
+
+def msla_linear_attention_backward(qkv, d_att, heads, head_dim, eps=1e-15, d_qkv=None, workspace=None, stream=None):
+    """Gradient of ReLU linear attention: qkv [B, ..., 3*heads*d], d_att [B, ..., heads*d] -> d_qkv like qkv."""
+    _dev(qkv, d_att, d_qkv, workspace)
+    B = qkv.shape[0]
+    N = qkv.numel() // (B * qkv.shape[-1])
+    if d_qkv is None:
+        d_qkv = torch.empty_like(qkv)
+    if workspace is None:
+        workspace = torch.empty(msla_linear_attention_backward_workspace_bytes(B, N, heads, head_dim, qkv.dtype),
+                                dtype=torch.uint8, device=qkv.device)
+    st = load_library().msla_linear_attention_backward(_ptr(qkv), _ptr(d_att), _ptr(d_qkv), _ptr(workspace),
+                                                       workspace.numel(), B, N, heads, head_dim, float(eps),
+                                                       _DTYPES[qkv.dtype], _stream(stream))
+    if st != MSLA_OK:
+        raise MslaError(st, "msla_linear_attention_backward")
+    return d_qkv

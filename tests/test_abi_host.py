@@ -34,7 +34,8 @@ def test_every_declared_symbol_is_exported(lib):
                           "msla_core_forward",
                           "msla_multiscale_state", "msla_multiscale_state_static", "msla_linear",
                           "msla_ffn_workspace_bytes", "msla_ffn_forward", "msla_block_workspace_bytes", "msla_block_forward",
-                          "msla_softmax_attention"}
+                          "msla_softmax_attention", "msla_linear_attention_backward_workspace_bytes",
+                          "msla_linear_attention_backward"}
     for n in names:
         assert getattr(lib, n) is not None
     from paper_2205_14756_amd import msla
