@@ -50,7 +50,7 @@
  *   out    [B, H, W, C] or [B, C, H, W], as x
  * No bias, normalisation or activation other than the ReLUs of Eq. (2).
  *
- * Supported: head_dim == 16; scales[a] in {3, 5}; n_scales <= 7;
+ * Supported: head_dim == 16; scales[a] in {3, 5, 7}; n_scales <= 7;
  * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  Anything else that is
  * otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
  */

@@ -509,6 +509,7 @@ hipError_t run_aggregate(const AggregateArgs& a, hipStream_t stream) {
     if (nblocks <= 0 || nblocks > 0x7fffffffL) return hipErrorInvalidValue;
     if (a.ks == 3) return run_aggregate_ks<T, 3>(a, (unsigned)nblocks, stream);
     if (a.ks == 5) return run_aggregate_ks<T, 5>(a, (unsigned)nblocks, stream);
+    if (a.ks == 7) return run_aggregate_ks<T, 7>(a, (unsigned)nblocks, stream);
     return hipErrorInvalidValue;
 }
 

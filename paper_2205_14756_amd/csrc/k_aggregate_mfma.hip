@@ -645,6 +645,7 @@ hipError_t run(const AggregateArgs& a, hipStream_t stream) {
     if ((long)a.H * a.W * widest * (long)sizeof(T) > 0x7fffffffL) return hipErrorNotSupported;
     if (a.ks == 3) return run_ks<T, 3>(a, (unsigned)nblocks, stream);
     if (a.ks == 5) return run_ks<T, 5>(a, (unsigned)nblocks, stream);
+    if (a.ks == 7) return hipErrorNotSupported;       // 7x7 takes the general kernel (the Toeplitz operands here span 8 input columns)
     return hipErrorInvalidValue;
 }
 

@@ -46,7 +46,7 @@ msla_status check_shape(int B, int H, int W, int heads, int head_dim, const int*
     if (head_dim != 16) return MSLA_ERR_UNSUPPORTED;
     if (n_scales > kMaxScales) return MSLA_ERR_UNSUPPORTED;
     for (int i = 0; i < n_scales; ++i)
-        if (scales[i] != 3 && scales[i] != 5) return MSLA_ERR_UNSUPPORTED;
+        if (scales[i] != 3 && scales[i] != 5 && scales[i] != 7) return MSLA_ERR_UNSUPPORTED;
     const long N = (long)H * W;
     const long T = N * B;
     if (N > (1L << 30) || T > (1L << 31) || (long)heads * 16 > (1L << 20)) return MSLA_ERR_UNSUPPORTED;

@@ -80,10 +80,11 @@ def test_workspace_bytes(lib):
     assert lib.msla_workspace_bytes(1, 64, 32, 32, 4, 16, None, 0, F32, None) == INVALID
     # unsupported
     assert _ws(lib, 1, 64, 32, 32, 8, 8, [5], F32)[0] == UNSUPPORTED   # head_dim != 16
-    assert _ws(lib, 1, 64, 32, 32, 4, 16, [7], F32)[0] == UNSUPPORTED
+    assert _ws(lib, 1, 64, 32, 32, 4, 16, [9], F32)[0] == UNSUPPORTED   # kernel sizes other than 3, 5, 7
+    assert _ws(lib, 1, 64, 32, 32, 4, 16, [7], F32)[0] == OK
     assert _ws(lib, 1, 60, 32, 32, 4, 16, [5], F32)[0] == UNSUPPORTED  # C not a multiple of 16
     # a failed query leaves *bytes alone
-    assert _ws(lib, 1, 64, 32, 32, 4, 16, [7], F32)[1] == 12345
+    assert _ws(lib, 1, 64, 32, 32, 4, 16, [9], F32)[1] == 12345
 
 
 def _fwd(lib, x=0x1000, wq=0x1000, wd=0x1000, wg=0x1000, wp=0x1000, out=0x2000, ws=0x3000, ws_bytes=1 << 40,

@@ -168,6 +168,9 @@ STATE_CASES = [
     (1, 9, 5, 2, ()),          # no aggregated scale
     (3, 40, 33, 2, (5,)),
     (8, 64, 64, 16, (5,)),     # enough (image, head) pairs that a workgroup walks over several tiles
+    (1, 20, 41, 2, (7,)),      # 7x7 aggregation (general kernel for every storage type)
+    (2, 5, 4, 1, (7,)),        # ... on a map smaller than the kernel
+    (1, 33, 35, 3, (5, 7)),    # a matrix-core scale and a general-kernel scale in one module
 ]
 
 
@@ -214,6 +217,7 @@ def test_multiscale_state_and_core(dtype, B, H, W, heads, scales):
     (2, 512, 7, 9, 32, (5,)),       # 64 head-branches (1024 slots), 512 input channels
     (1, 384, 6, 11, 24, (5,)),      # 48 head-branches (768 slots), ragged 32-token tiles
     (1, 640, 5, 8, 40, (5,)),       # 80 head-branches: beyond the long-contraction kernel, tiled forms
+    (2, 64, 19, 23, 4, (3, 5, 7)),  # four branches, 7x7 among them
 ])
 def test_forward_small(dtype, B, C, H, W, heads, scales):
     d = 16
