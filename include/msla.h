@@ -51,8 +51,10 @@
  * No bias, normalisation or activation other than the ReLUs of Eq. (2).
  *
  * Supported: head_dim == 16; scales[a] in {3, 5, 7}; n_scales <= 7;
- * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  Anything else that is
- * otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
+ * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  msla_forward (and the
+ * workspace query) also take head_dim 8 and 32 (MSLA_NHWC, no options; plain,
+ * untuned kernels: the matrix-core kernels are built around head_dim 16).  Anything
+ * else that is otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
  */
 #ifndef MSLA_H_
 #define MSLA_H_

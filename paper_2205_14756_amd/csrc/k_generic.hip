@@ -1,0 +1,216 @@
+// The module for head sizes other than 16 (Section 3.1 fixes only "d channels per group"; 8 and 32 are
+// the other sizes the architecture family uses): multi-scale aggregation, the Eq. (3) state and the
+// normalise-and-apply pass as plain vector-ALU kernels templated on the head size D.  They follow the
+// definitions step by step, fp32 sums throughout, the same storage points as the head-size-16 path
+// (projected Q/K/V and the Q tokens of every branch are stored in the storage type; aggregated K and V
+// only feed the state), and are not tuned: the matrix-core kernels are built around 16 x 16 tiles.
+//
+//   generic_branch_state_kernel   one branch (raw, or depthwise k x k + grouped 1x1) of one (image, head,
+//                                 chunk of 64-token groups): writes that branch's Q tokens, accumulates
+//                                 KV = sum_n relu(K_n)^T [V_n, 1] into a per-workgroup partial state
+//   generic_state_finalize_kernel fixed-order sum of the partial states
+//   generic_apply_kernel          att_n = relu(Q_n) KV[:, :D] / (relu(Q_n) KV[:, D] + eps)
+#include "msla_device.h"
+#include "msla_kernels.h"
+
+namespace msla {
+namespace {
+
+constexpr int kGenThreads = 256;
+constexpr int kGenTokens = 64;       // tokens per step of a workgroup
+
+template <class T, int D>
+__global__ __launch_bounds__(kGenThreads) void generic_branch_state_kernel(
+    const T* __restrict__ qkv, const T* __restrict__ w_dw, const T* __restrict__ w_gpw, T* __restrict__ q_ms,
+    float* __restrict__ partials, int H, int W, int heads, int S, int branch, int ks, int nchunks, int groups_per_chunk) {
+    constexpr int kState = D * (D + 1);
+    constexpr int kAcc = (kState + kGenThreads - 1) / kGenThreads;
+    __shared__ float dw[kGenTokens][3 * D];       // depthwise sums (or, raw branch, the tokens themselves)
+    __shared__ float rk[kGenTokens][D];           // rectified K of the branch
+    __shared__ float vv[kGenTokens][D];           // V of the branch
+    const int h = blockIdx.x % heads;
+    const int chunk = (blockIdx.x / heads) % nchunks;
+    const int b = blockIdx.x / (heads * nchunks);
+    const int N = H * W;
+    const int Ct = heads * D;
+    const long ts = 3L * Ct;                                   // elements from token to token of qkv
+    const T* img = qkv + (long)b * N * ts + (long)h * 3 * D;   // this head's 3*D channels of token 0
+    const int P = (ks - 1) / 2;
+    const T* wd = w_dw + (long)h * 3 * D * ks * ks;            // [3*D][ks][ks] of this head
+    const T* wg = w_gpw + (long)h * 3 * D * D;                 // [3*D][D] of this head
+
+    float acc[kAcc];
+#pragma unroll
+    for (int i = 0; i < kAcc; ++i) acc[i] = 0.f;
+
+    const int n_groups = (N + kGenTokens - 1) / kGenTokens;
+    const int g_begin = chunk * groups_per_chunk;
+    const int g_end = g_begin + groups_per_chunk < n_groups ? g_begin + groups_per_chunk : n_groups;
+    for (int g = g_begin; g < g_end; ++g) {
+        const int n0 = g * kGenTokens;
+        // ---- A: depthwise k x k sums of the group's tokens (zero padding), or the raw tokens
+        for (int it = threadIdx.x; it < kGenTokens * 3 * D; it += kGenThreads) {
+            const int tk = it / (3 * D), c = it - tk * (3 * D);
+            const int n = n0 + tk;
+            float s = 0.f;
+            if (n < N) {
+                if (ks == 0) {
+                    s = Traits<T>::to_f32(img[(long)n * ts + c]);
+                } else {
+                    const int y = n / W, x = n - y * W;
+                    for (int u = 0; u < ks; ++u) {
+                        const int yy = y + u - P;
+                        if (yy < 0 || yy >= H) continue;
+                        for (int v = 0; v < ks; ++v) {
+                            const int xx = x + v - P;
+                            if (xx < 0 || xx >= W) continue;
+                            s = fmaf(Traits<T>::to_f32(wd[(c * ks + u) * ks + v]),
+                                     Traits<T>::to_f32(img[((long)yy * W + xx) * ts + c]), s);
+                        }
+                    }
+                }
+            }
+            dw[tk][c] = s;
+        }
+        __syncthreads();
+        // ---- B: grouped 1x1 (D -> D inside each of Q, K, V); Q is stored, relu(K) and V go on to the state
+        for (int it = threadIdx.x; it < kGenTokens * 3 * D; it += kGenThreads) {
+            const int tk = it / (3 * D), c = it - tk * (3 * D);
+            const int t = c / D, o = c - t * D;
+            const int n = n0 + tk;
+            float s;
+            if (ks == 0) {
+                s = dw[tk][c];
+            } else {
+                s = 0.f;
+#pragma unroll 8
+                for (int e = 0; e < D; ++e) s = fmaf(Traits<T>::to_f32(wg[(long)c * D + e]), dw[tk][t * D + e], s);
+            }
+            if (t == 0) {
+                if (n < N) q_ms[((long)b * N + n) * ((long)S * Ct) + (long)(branch * heads + h) * D + o] = Traits<T>::from_f32(s);
+            } else if (t == 1) {
+                rk[tk][o] = n < N ? fmaxf(s, 0.f) : 0.f;       // Eq. (2); tokens past the image contribute nothing
+            } else {
+                vv[tk][o] = s;
+            }
+        }
+        __syncthreads();
+        // ---- C: KV[e][f] += sum_n relu(K_n[e]) * (f < D ? V_n[f] : 1)
+#pragma unroll
+        for (int i = 0; i < kAcc; ++i) {
+            const int idx = threadIdx.x + i * kGenThreads;
+            if (idx < kState) {
+                const int e = idx / (D + 1), f = idx - e * (D + 1);
+                float s = acc[i];
+                if (f < D) {
+                    for (int tk = 0; tk < kGenTokens; ++tk) s = fmaf(rk[tk][e], vv[tk][f], s);
+                } else {
+                    for (int tk = 0; tk < kGenTokens; ++tk) s += rk[tk][e];
+                }
+                acc[i] = s;
+            }
+        }
+        __syncthreads();
+    }
+    float* out = partials + ((((long)b * S + branch) * heads + h) * nchunks + chunk) * kState;
+#pragma unroll
+    for (int i = 0; i < kAcc; ++i) {
+        const int idx = threadIdx.x + i * kGenThreads;
+        if (idx < kState) out[idx] = acc[i];
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kGenThreads) void generic_state_finalize_kernel(const float* __restrict__ partials,
+                                                                             float* __restrict__ kv32, int nchunks) {
+    constexpr int kState = D * (D + 1);
+    const long sid = blockIdx.x;
+    for (int j = threadIdx.x; j < kState; j += kGenThreads) {
+        float v = 0.f;
+        for (int c = 0; c < nchunks; ++c) v += partials[(sid * nchunks + c) * kState + j];     // chunk order: reproducible
+        kv32[sid * kState + j] = v;
+    }
+}
+
+// one workgroup = 256 tokens of one (image, head-branch m): a thread per token
+template <class T, int D>
+__global__ __launch_bounds__(kGenThreads) void generic_apply_kernel(const T* __restrict__ q_ms, const float* __restrict__ kv32,
+                                                                    T* __restrict__ att, int N, int n_hb, int blocks_per_image,
+                                                                    float eps) {
+    constexpr int kState = D * (D + 1);
+    __shared__ float St[kState];
+    const int m = blockIdx.x % n_hb;
+    const int nb = (blockIdx.x / n_hb) % blocks_per_image;
+    const int b = blockIdx.x / (n_hb * blocks_per_image);
+    for (int j = threadIdx.x; j < kState; j += kGenThreads) St[j] = kv32[((long)b * n_hb + m) * kState + j];
+    __syncthreads();
+    const int n = nb * kGenThreads + threadIdx.x;
+    if (n >= N) return;
+    const long row = ((long)b * N + n) * ((long)n_hb * D) + (long)m * D;
+    float num[D];
+#pragma unroll
+    for (int f = 0; f < D; ++f) num[f] = 0.f;
+    float den = eps;
+#pragma unroll
+    for (int e = 0; e < D; ++e) {
+        const float rq = fmaxf(Traits<T>::to_f32(q_ms[row + e]), 0.f);
+        den = fmaf(rq, St[e * (D + 1) + D], den);
+#pragma unroll
+        for (int f = 0; f < D; ++f) num[f] = fmaf(rq, St[e * (D + 1) + f], num[f]);
+    }
+    const float inv = 1.0f / den;
+#pragma unroll
+    for (int f = 0; f < D; ++f) att[row + f] = Traits<T>::from_f32(num[f] * inv);
+}
+
+template <class T, int D>
+hipError_t run_generic(const GenericArgs& a, hipStream_t stream) {
+    const int N = a.H * a.W;
+    const int n_groups = (N + kGenTokens - 1) / kGenTokens;
+    const int gpc = (n_groups + a.nchunks - 1) / a.nchunks;
+    const long nb = (long)a.B * a.heads * a.nchunks;
+    if (nb <= 0 || nb > 0x7fffffffL) return hipErrorInvalidValue;
+    const int S = 1 + a.n_scales;
+    size_t dw_off = 0;
+    for (int s = 0; s < S; ++s) {
+        const int ks = s == 0 ? 0 : a.scales[s - 1];
+        const T* wdw = s == 0 ? nullptr : (const T*)a.w_dw + dw_off;
+        const T* wgp = s == 0 ? nullptr : (const T*)a.w_gpw + (size_t)(s - 1) * 3 * a.heads * D * D;
+        if (s > 0) dw_off += (size_t)3 * a.heads * D * ks * ks;
+        hipLaunchKernelGGL((generic_branch_state_kernel<T, D>), dim3((unsigned)nb), dim3(kGenThreads), 0, stream,
+                           (const T*)a.qkv, wdw, wgp, (T*)a.q_ms, a.partials, a.H, a.W, a.heads, S, s, ks, a.nchunks, gpc);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int n_states = a.B * S * a.heads;
+    hipLaunchKernelGGL((generic_state_finalize_kernel<D>), dim3((unsigned)n_states), dim3(kGenThreads), 0, stream, a.partials,
+                       a.kv32, a.nchunks);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int bpi = (N + kGenThreads - 1) / kGenThreads;
+    const long nb2 = (long)a.B * S * a.heads * bpi;
+    if (nb2 > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((generic_apply_kernel<T, D>), dim3((unsigned)nb2), dim3(kGenThreads), 0, stream, (const T*)a.q_ms, a.kv32,
+                       (T*)a.att, N, S * a.heads, bpi, a.eps);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t run_generic_d(const GenericArgs& a, hipStream_t stream) {
+    if (a.head_dim == 8) return run_generic<T, 8>(a, stream);
+    if (a.head_dim == 32) return run_generic<T, 32>(a, stream);
+    return hipErrorNotSupported;
+}
+
+}  // namespace
+
+hipError_t launch_generic_core(int dt, const GenericArgs& a, hipStream_t stream) {
+    switch (dt) {
+        case 0: return run_generic_d<float>(a, stream);
+        case 1: return run_generic_d<_Float16>(a, stream);
+        case 2: return run_generic_d<__bf16>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace msla

@@ -185,6 +185,71 @@ int compute_units() {
 }
 }  // namespace msla
 
+namespace {
+
+// ---- head sizes 8 and 32: projection -> generic core (k_generic.hip) -> projection
+struct GenericPlan {
+    long T;
+    int Ct, S, nchunks;
+    size_t qkv, q_ms, att, partials, kv32, total;
+};
+
+bool generic_head_dim(int head_dim) { return head_dim == 8 || head_dim == 32; }
+
+msla_status generic_plan(int B, int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales, int dt,
+                         GenericPlan* p) {
+    if (B <= 0 || C <= 0 || H <= 0 || W <= 0 || heads <= 0 || n_scales < 0) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > 0 && scales == nullptr) return MSLA_ERR_INVALID_ARG;
+    if (dt != MSLA_F32 && dt != MSLA_F16 && dt != MSLA_BF16) return MSLA_ERR_INVALID_ARG;
+    for (int i = 0; i < n_scales; ++i)
+        if (scales[i] < 1 || scales[i] % 2 == 0) return MSLA_ERR_INVALID_ARG;
+    if (n_scales > kMaxScales) return MSLA_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_scales; ++i)
+        if (scales[i] != 3 && scales[i] != 5 && scales[i] != 7) return MSLA_ERR_UNSUPPORTED;
+    const long N = (long)H * W;
+    if (N > (1L << 30) || N * B > (1L << 31) || (long)heads * head_dim > (1L << 20)) return MSLA_ERR_UNSUPPORTED;
+    if (C % 16 != 0 || (heads * head_dim) % 16 != 0) return MSLA_ERR_UNSUPPORTED;
+    const size_t e = elem_size((msla_dtype)dt);
+    p->T = N * B; p->Ct = heads * head_dim; p->S = 1 + n_scales;
+    const long groups = (N + 63) / 64;
+    long want = (512 + (long)B * heads - 1) / ((long)B * heads);
+    if (want > groups) want = groups;
+    if (want < 1) want = 1;
+    p->nchunks = (int)want;
+    const size_t n_states = (size_t)B * p->S * heads, state = (size_t)head_dim * (head_dim + 1) * sizeof(float);
+    size_t off = 0;
+    p->qkv = off;      off += align_up((size_t)p->T * 3 * p->Ct * e);
+    p->q_ms = off;     off += align_up((size_t)p->T * p->S * p->Ct * e);
+    p->att = off;      off += align_up((size_t)p->T * p->S * p->Ct * e);
+    p->partials = off; off += align_up(n_states * p->nchunks * state);
+    p->kv32 = off;     off += align_up(n_states * state);
+    p->total = off;
+    return MSLA_OK;
+}
+
+msla_status generic_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw, const void* w_proj,
+                            void* out, void* workspace, size_t workspace_bytes, int B, int C, int H, int W, int heads,
+                            int head_dim, const int* scales, int n_scales, float eps, msla_dtype dt, hipStream_t hs) {
+    GenericPlan p;
+    const msla_status st = generic_plan(B, C, H, W, heads, head_dim, scales, n_scales, (int)dt, &p);
+    if (st != MSLA_OK) return st;
+    if (workspace_bytes < p.total) return MSLA_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    if (msla::launch_linear((int)dt, x, w_qkv, ws + p.qkv, p.T, C, 3 * p.Ct, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    msla::GenericArgs a;
+    a.qkv = ws + p.qkv; a.w_dw = w_dw; a.w_gpw = w_gpw; a.q_ms = ws + p.q_ms;
+    a.partials = reinterpret_cast<float*>(ws + p.partials); a.kv32 = reinterpret_cast<float*>(ws + p.kv32);
+    a.att = ws + p.att;
+    a.B = B; a.H = H; a.W = W; a.heads = heads; a.head_dim = head_dim; a.n_scales = n_scales;
+    for (int i = 0; i < n_scales; ++i) a.scales[i] = scales[i];
+    a.nchunks = p.nchunks; a.eps = eps;
+    if (msla::launch_generic_core((int)dt, a, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_linear((int)dt, ws + p.att, w_proj, out, p.T, p.S * p.Ct, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    return MSLA_OK;
+}
+
+}  // namespace
+
 namespace msla {
 int multiscale_state_small(const void* qkv, const void* w_dw, const void* w_gpw, void* q_ms, float* kv,
                            void* scratch, size_t scratch_bytes, int B, int H, int W, int heads, int head_dim,
@@ -207,6 +272,12 @@ const char* msla_error_string(msla_status status) {
 msla_status msla_workspace_bytes(int B, int C, int H, int W, int heads, int head_dim, const int* scales,
                                  int n_scales, msla_dtype dt, size_t* bytes) {
     if (bytes == nullptr || C <= 0) return MSLA_ERR_INVALID_ARG;
+    if (generic_head_dim(head_dim)) {
+        GenericPlan p;
+        const msla_status gst = generic_plan(B, C, H, W, heads, head_dim, scales, n_scales, (int)dt, &p);
+        if (gst == MSLA_OK) *bytes = p.total;
+        return gst;
+    }
     Shape s;
     const msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
     if (st != MSLA_OK) return st;
@@ -226,6 +297,15 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     if (n_scales > 0 && (!w_dw || !w_gpw)) return MSLA_ERR_INVALID_ARG;
     if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
     if (layout != MSLA_NHWC && layout != MSLA_NCHW) return MSLA_ERR_INVALID_ARG;
+    if (generic_head_dim(head_dim)) {
+        // head sizes 8 and 32: the plain kernels; token-major only, no options, no stage events, no residual
+        if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
+            !aligned16(w_dw) || !aligned16(w_gpw))
+            return MSLA_ERR_INVALID_ARG;
+        if (layout != MSLA_NHWC || options != 0 || events != nullptr || residual != nullptr) return MSLA_ERR_UNSUPPORTED;
+        return generic_forward(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads, head_dim,
+                               scales, n_scales, eps, dt, static_cast<hipStream_t>(stream));
+    }
     if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
         !aligned16(w_dw) || !aligned16(w_gpw))
         return MSLA_ERR_INVALID_ARG;

@@ -107,6 +107,24 @@ hipError_t launch_linear_attention_backward(int dt, const void* qkv, const void*
                                             int N, int heads, int nchunks, int tiles_per_chunk, float eps,
                                             hipStream_t stream);
 
+// The module's core (aggregation, Eq. (3) state, normalise-and-apply) for head sizes 8 and 32 (k_generic.hip):
+// att [T, S*heads*head_dim] from the projected map qkv [T, 3*heads*head_dim].
+struct GenericArgs {
+    const void* qkv;
+    const void* w_dw;       // concat over scales of [3*Ct, k, k]
+    const void* w_gpw;      // [A, 3*Ct, head_dim]
+    void* q_ms;             // [T, S*Ct] work buffer: the Q tokens of every branch
+    float* partials;        // [B*S*heads*nchunks, head_dim*(head_dim+1)]
+    float* kv32;            // [B*S*heads, head_dim*(head_dim+1)]
+    void* att;
+    int B, H, W, heads, head_dim;
+    int n_scales;
+    int scales[8];
+    int nchunks;
+    float eps;
+};
+hipError_t launch_generic_core(int dt, const GenericArgs& a, hipStream_t stream);
+
 // dst[b][c][r] = src[b][r][c] for every b < batch: the change between [B, C, H*W] and [B, H*W, C]
 hipError_t launch_transpose(int dt, const void* src, void* dst, long batch, int rows, int cols,
                             hipStream_t stream);

@@ -79,7 +79,9 @@ def test_workspace_bytes(lib):
     assert lib.msla_workspace_bytes(1, 64, 32, 32, 4, 16, None, 1, F32, ctypes.byref(ctypes.c_size_t())) == INVALID
     assert lib.msla_workspace_bytes(1, 64, 32, 32, 4, 16, None, 0, F32, None) == INVALID
     # unsupported
-    assert _ws(lib, 1, 64, 32, 32, 8, 8, [5], F32)[0] == UNSUPPORTED   # head_dim != 16
+    assert _ws(lib, 1, 64, 32, 32, 8, 8, [5], F32)[0] == OK            # head_dim 8 and 32: the plain kernels
+    assert _ws(lib, 1, 64, 32, 32, 2, 32, [5], F16)[0] == OK
+    assert _ws(lib, 1, 96, 32, 32, 4, 24, [5], F32)[0] == UNSUPPORTED  # head_dim not in {8, 16, 32}
     assert _ws(lib, 1, 64, 32, 32, 4, 16, [9], F32)[0] == UNSUPPORTED   # kernel sizes other than 3, 5, 7
     assert _ws(lib, 1, 64, 32, 32, 4, 16, [7], F32)[0] == OK
     assert _ws(lib, 1, 60, 32, 32, 4, 16, [5], F32)[0] == UNSUPPORTED  # C not a multiple of 16
@@ -109,7 +111,9 @@ def test_forward_rejects_bad_arguments_before_launching(lib):
     assert _fwd(lib, scales=(2,)) == INVALID
     assert _fwd(lib, H=0) == INVALID
     assert _fwd(lib, layout=1, C=256) == UNSUPPORTED  # channel-planar needs C <= 2 * heads * head_dim
-    assert _fwd(lib, d=32) == UNSUPPORTED
+    assert _fwd(lib, d=24, C=96) == UNSUPPORTED
+    assert _fwd(lib, d=32, heads=2, layout=1) == UNSUPPORTED     # head_dim 8 / 32: token-major only
+    assert _fwd(lib, d=32, heads=2, ws_bytes=1024) == WORKSPACE
     assert _fwd(lib, scales=(9,)) == UNSUPPORTED
     assert _fwd(lib, ws_bytes=1024) == WORKSPACE
 

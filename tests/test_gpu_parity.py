@@ -317,6 +317,22 @@ def test_forward_raw_branch_state_on_the_vector_alus(dtype, B, C, H, W, heads):
     check_module(t, dtype, heads, 16, (), options=msla.MSLA_OPT_STATE_VALU, stages=False)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("B,C,H,W,heads,d,scales", [
+    (1, 64, 9, 13, 8, 8, (5,)),         # head size 8
+    (2, 64, 12, 21, 2, 32, (5,)),       # head size 32
+    (1, 32, 1, 1, 4, 8, (3, 5)),        # a single token
+    (2, 96, 17, 10, 3, 32, (3, 7)),     # three branches, ragged 64-token groups, C != heads * head size
+    (1, 128, 30, 40, 16, 8, ()),        # no aggregated scale
+    (1, 128, 64, 64, 4, 32, (5,)),      # several chunks per state
+])
+def test_forward_other_head_sizes(dtype, B, C, H, W, heads, d, scales):
+    """Head sizes 8 and 32 (the plain kernels of k_generic.hip): the same bar, the same protocol."""
+    print(f"forward {dtype} B={B} C={C} {H}x{W} heads={heads} head size {d} scales={scales}", flush=True)
+    t = wk.random_module(C * 10 + H + d, dtype, B, C, H, W, heads, d, scales)
+    check_module(t, dtype, heads, d, scales, stages=False)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_forward_benchmark_configs_full_size(cfg):
     """The five workload shapes at full size, in the launch configuration the bench times."""
