@@ -89,8 +89,10 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The kernel's body for workgroup `bid` of `nblocks` (a launch may hold the workgroups of two scales, see
+// aggregate_mfma_pair_kernel).
 template <class T, int KS, bool kCopyRawQ>
-__global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs a) {
+__device__ __forceinline__ void aggregate_mfma_body(const AggregateArgs& a, unsigned bid, unsigned nblocks) {
     typedef Traits<T> Tr;
     typedef typename Tr::Frag Frag;
     typedef typename Tr::Vec Vec;
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     extern __shared__ __attribute__((aligned(16))) char lds[];
     float* red = (float*)lds;             // reused after the last tile
 
-    const unsigned Lid = xcd_remap(blockIdx.x, gridDim.x);
+    const unsigned Lid = xcd_remap(bid, nblocks);
     const int h = Lid % a.heads;
     const int chunk = (Lid / a.heads) % a.nchunks;
     const int b = Lid / (a.heads * a.nchunks);
@@ -617,6 +619,23 @@ __global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs 
     }
 }
 
+template <class T, int KS, bool kCopyRawQ>
+__global__ __launch_bounds__(kThreads) void aggregate_mfma_kernel(AggregateArgs a) {
+    aggregate_mfma_body<T, KS, kCopyRawQ>(a, blockIdx.x, gridDim.x);
+}
+
+// Two aggregated scales in one launch: the first half of the grid works on scale A, the second on scale
+// B (each half a multiple of 8 workgroups, so a workgroup's position among the XCDs is what it would be
+// in a launch of its own).  Nothing is shared between the halves; what the single launch buys is that
+// the compute units never drain between the two scales: a unit that finishes its scale-A workgroup goes
+// straight on to a scale-B one.
+template <class T, int KSA, int KSB>
+__global__ __launch_bounds__(kThreads) void aggregate_mfma_pair_kernel(AggregateArgs a0, AggregateArgs a1) {
+    const unsigned half = gridDim.x >> 1;
+    if (blockIdx.x < half) aggregate_mfma_body<T, KSA, false>(a0, blockIdx.x, half);
+    else aggregate_mfma_body<T, KSB, false>(a1, blockIdx.x - half, half);
+}
+
 template <class T, int KS>
 hipError_t run_ks(const AggregateArgs& a, unsigned nblocks, hipStream_t stream) {
     constexpr int kLds = MLds<KS>::kBytes;
@@ -649,7 +668,43 @@ hipError_t run(const AggregateArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
+template <class T, int KSA, int KSB>
+hipError_t run_pair_ks(const AggregateArgs& a0, const AggregateArgs& a1, unsigned nblocks, hipStream_t stream) {
+    constexpr int kLds = MLds<KSA>::kBytes > MLds<KSB>::kBytes ? MLds<KSA>::kBytes : MLds<KSB>::kBytes;
+    const hipError_t e = allow_dynamic_lds<aggregate_mfma_pair_kernel<T, KSA, KSB>>(kLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((aggregate_mfma_pair_kernel<T, KSA, KSB>), dim3(2 * nblocks), dim3(kThreads), kLds, stream, a0, a1);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t run_pair(const AggregateArgs& a0, const AggregateArgs& a1, hipStream_t stream) {
+    const long nblocks = (long)a0.B * a0.heads * a0.nchunks;
+    if (nblocks <= 0 || 2 * nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    if (nblocks % 8 != 0 || a0.copy_raw_q || a1.copy_raw_q) return hipErrorNotSupported;
+    for (const AggregateArgs* a : {&a0, &a1}) {
+        if ((const char*)a->v != (const char*)a->k + 16 * sizeof(T) || a->v_ts != a->k_ts || a->v_hs != a->k_hs)
+            return hipErrorNotSupported;
+        const long widest = std::max(std::max(a->q_ts, a->k_ts), (long)a->S * a->heads * 16);
+        if ((long)a->H * a->W * widest * (long)sizeof(T) > 0x7fffffffL) return hipErrorNotSupported;
+    }
+    if (a0.ks == 3 && a1.ks == 5) return run_pair_ks<T, 3, 5>(a0, a1, (unsigned)nblocks, stream);
+    if (a0.ks == 5 && a1.ks == 3) return run_pair_ks<T, 5, 3>(a0, a1, (unsigned)nblocks, stream);
+    return hipErrorNotSupported;
+}
+
 }  // namespace
+
+hipError_t launch_aggregate_mfma_pair(int dt, const AggregateArgs& a0, const AggregateArgs& a1, hipStream_t stream) {
+#ifdef MSLA_AGG_NO_MFMA
+    return hipErrorNotSupported;
+#endif
+    switch (dt) {
+        case 1: return run_pair<_Float16>(a0, a1, stream);
+        case 2: return run_pair<__bf16>(a0, a1, stream);
+    }
+    return hipErrorNotSupported;
+}
 
 hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream) {
 #ifdef MSLA_AGG_NO_MFMA

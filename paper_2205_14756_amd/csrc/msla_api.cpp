@@ -133,7 +133,25 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
         a.state_valu = (options & MSLA_OPT_STATE_VALU) ? 1 : 0;
         if (msla::launch_raw_state((int)dt, a, stream) != hipSuccess) return MSLA_ERR_LAUNCH;
     }
-    for (int i = 0; i < s.n_scales && aggregate; ++i) {
+    auto aim = [&](msla::AggregateArgs& g, int i) {
+        g.w_dw = static_cast<const char*>(w_dw) + dw_weight_elems(s, i) * e;
+        g.w_gpw = static_cast<const char*>(w_gpw) + (size_t)i * 3 * s.Ct * 16 * e;
+        g.ks = s.scales[i];
+        g.branch = i + 1;
+        g.do_raw = (i == 0);
+        g.copy_raw_q = (i == 0) ? copy_raw_q : 0;
+    };
+    int first = 0;
+    if (aggregate && s.n_scales == 2 && dt != MSLA_F32 && !(options & MSLA_OPT_GENERAL_AGGREGATION)) {
+        // a 3x3 and a 5x5 scale: both in one launch, so the compute units do not drain between them
+        msla::AggregateArgs a0 = a, a1 = a;
+        aim(a0, 0);
+        aim(a1, 1);
+        const hipError_t e_pair = msla::launch_aggregate_mfma_pair((int)dt, a0, a1, stream);
+        if (e_pair == hipSuccess) first = 2;
+        else if (e_pair != hipErrorNotSupported) return MSLA_ERR_LAUNCH;
+    }
+    for (int i = first; i < s.n_scales && aggregate; ++i) {
         a.w_dw = static_cast<const char*>(w_dw) + dw_weight_elems(s, i) * e;
         a.w_gpw = static_cast<const char*>(w_gpw) + (size_t)i * 3 * s.Ct * 16 * e;
         a.ks = s.scales[i];

@@ -49,6 +49,10 @@ hipError_t launch_aggregate(int dt, const AggregateArgs& a, hipStream_t stream);
 // hipErrorNotSupported without launching when one image's maps span 2^31 bytes or more.
 hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t stream);
 
+// Two aggregated scales (3x3 and 5x5, either order) of the same module in one launch; hipErrorNotSupported,
+// without launching, for anything else (then the caller launches them one by one).
+hipError_t launch_aggregate_mfma_pair(int dt, const AggregateArgs& a0, const AggregateArgs& a1, hipStream_t stream);
+
 // Raw-branch-only variant for n_scales == 0 (no convolution): state of branch 0, optional Q copy.
 hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream);
 
