@@ -189,7 +189,7 @@ msla_status msla_multiscale_state_static(const void* qkv, const void* w_dw, cons
  *     out = y + W2 g  1x1, hidden -> C, no activation, residual; no bias, no normalisation.
  *   y, out [B, H, W, C] (token-major);  w1 [hidden, C];  w_dw [hidden, 3, 3];  w2 [C, hidden].
  * C and hidden multiples of 16 (else MSLA_ERR_UNSUPPORTED).  out may not alias y.
- * workspace: msla_ffn_workspace_bytes (two [B,H,W,hidden] maps). */
+ * workspace: msla_ffn_workspace_bytes (one [B,H,W,hidden] map: the activated expand result). */
 msla_status msla_ffn_workspace_bytes(int B, int C, int H, int W, int hidden, msla_dtype dt, size_t* bytes);
 msla_status msla_ffn_forward(const void* y, const void* w1, const void* w_dw, const void* w2, void* out,
                              void* workspace, size_t workspace_bytes,

@@ -481,7 +481,7 @@ msla_status msla_core_forward(const void* qkv, const void* w_dw, const void* w_g
 static bool ffn_shape_ok(int B, int C, int H, int W, int hidden) {
     return B > 0 && C > 0 && H > 0 && W > 0 && hidden > 0;
 }
-static size_t ffn_ws_bytes(long T, int hidden, msla_dtype dt) { return 2 * align_up((size_t)T * hidden * elem_size(dt)); }
+static size_t ffn_ws_bytes(long T, int hidden, msla_dtype dt) { return align_up((size_t)T * hidden * elem_size(dt)); }
 
 msla_status msla_ffn_workspace_bytes(int B, int C, int H, int W, int hidden, msla_dtype dt, size_t* bytes) {
     if (!bytes || !ffn_shape_ok(B, C, H, W, hidden)) return MSLA_ERR_INVALID_ARG;
@@ -504,10 +504,10 @@ msla_status msla_ffn_forward(const void* y, const void* w1, const void* w_dw, co
     if (workspace_bytes < ffn_ws_bytes(T, hidden, dt)) return MSLA_ERR_WORKSPACE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     char* h_pre = static_cast<char*>(workspace);
-    char* g = h_pre + align_up((size_t)T * hidden * elem_size(dt));
     if (msla::launch_linear_act((int)dt, y, w1, h_pre, T, C, hidden, (int)act, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
-    if (msla::launch_ffn_dw((int)dt, h_pre, w_dw, g, B, H, W, hidden, (int)act, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
-    if (msla::launch_linear_residual((int)dt, g, w2, y, out, T, hidden, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    // depthwise 3x3 + activation + hidden -> C projection + residual in one kernel (the depthwise result stays on chip)
+    if (msla::launch_ffn_dw_project((int)dt, h_pre, w_dw, w2, y, out, B, H, W, hidden, C, (int)act, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
     return MSLA_OK;
 }
 

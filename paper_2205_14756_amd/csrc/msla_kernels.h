@@ -90,9 +90,9 @@ inline bool small_product(int dt, long n_tokens, int K, int c_out) {
 }
 
 // The FFN+DWConv half of the building block (k_ffn.hip).  act: 0 ReLU, 1 hard-swish.
-//   g[b,y,x,c] = act(sum_{u,v} w_dw[c,u,v] * h[b, y+u-1, x+v-1, c])     (zero outside the map)
-hipError_t launch_ffn_dw(int dt, const void* h, const void* w_dw, void* g, int B, int H, int W, int E, int act,
-                         hipStream_t stream);
+//   out[n, c] = res[n, c] + sum_e act(DW3x3(h))[n, e] * w2[c, e]   (one kernel: the depthwise result stays on chip)
+hipError_t launch_ffn_dw_project(int dt, const void* h, const void* w_dw, const void* w2, const void* res, void* out, int B,
+                                 int H, int W, int E, int c_out, int act, hipStream_t stream);
 //   y[n, o] = act(sum_c x[n, c] * w[o, c])   (k_project.hip; the activation is applied to the fp32 sums)
 hipError_t launch_linear_act(int dt, const void* x, const void* w, void* y, long n_tokens, int c_in, int c_out, int act,
                              hipStream_t stream);
