@@ -378,6 +378,40 @@ def main():
                 "frac_on_fused_bytes": round(fused_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "frac_on_bytes_as_built": round(built_b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del w1, wfd, w2, bws, bout
+        # A chain of building blocks on the token grids of a 1024 x 2048 image (Section 4: the Cityscapes
+        # resolution): 3 blocks at stride 16 (64 x 128 tokens, C = 128, 8 heads) and 4 blocks at stride 32
+        # (32 x 64 tokens, C = 256, 16 heads), batch 1, fp16, hidden = 4C, hard-swish, scales {raw, 5x5}.
+        # The depths are this bench's choice (the paper's configurations are not in its text), and stem,
+        # early stages, downsampling and head are not part of it: the paper's whole-model figures stand
+        # beside it as context only.
+        chain = []
+        for (cc, hh, ww, nh, depth) in ((128, 64, 128, 8, 3), (256, 32, 64, 16, 4)):
+            cw = wk.Workload("chain", "f16", 1, cc, hh, ww, nh, 16, (5,), seed=77 + cc)
+            ct = wk.make_inputs(cw)
+            cf = wk.ffn_weights(78 + cc, "f16", cc, 4 * cc)
+            cdev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).half().cuda().contiguous()
+            args_ = [cdev(ct[k]) for k in ("w_qkv", "w_dw", "w_gpw", "w_proj")] + [cdev(cf[k]) for k in ("w1", "w_ffn_dw", "w2")]
+            xa, xb = cdev(ct["x"]), torch.empty((1, hh, ww, cc), dtype=torch.float16, device="cuda")
+            cws = torch.empty(msla.msla_block_workspace_bytes(1, cc, hh, ww, nh, 16, (5,), 4 * cc, torch.float16),
+                              dtype=torch.uint8, device="cuda")
+            chain.append((depth, xa, xb, args_, nh, cws))
+
+        def run_chain():
+            for depth, xa, xb, args_, nh, cws in chain:
+                src, dst = xa, xb
+                for _ in range(depth):
+                    msla.msla_block_forward(src, *args_, nh, 16, (5,), 1e-15, msla.MSLA_ACT_HSWISH, out=dst, workspace=cws,
+                                            stream=stream)
+                    src, dst = dst, src
+        for _ in range(100):
+            run_chain()
+        ms = timed(run_chain, 300)
+        others["block_chain_1024x2048"] = {
+            "entry": "msla_block_forward x 7 (3 at 64x128 tokens C=128, 4 at 32x64 tokens C=256)", "dtype": "f16",
+            "ms_per_image": round(ms, 5), "images_per_s": round(1e3 / ms, 1),
+            "context": "the paper's whole EfficientViT-B1 at this resolution: 175 images/s on an A100, TensorRT fp16 "
+                       "(Table 3); another machine, another scope (whole model), not a target"}
+        del chain
         # the backward pass of ReLU linear attention (gradient of Eq. (3)) on the headline shape: three passes
         # over the tokens (forward state: K, V; dS: Q, dAtt; gradients: Q, K, V, dAtt in, dQ, dK, dV out) =
         # 11 units of e*Ct*T
