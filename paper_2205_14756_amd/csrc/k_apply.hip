@@ -249,7 +249,11 @@ struct WsApply {
     static constexpr int kBuf = NS * kSlab;              // one attention tile or Q tile
     static constexpr int kQV = NS / 2;                   // 16-byte vectors per thread of a Q tile
     static constexpr int kWeightStage = kChanBlock * kRow;
-    static constexpr int kTiles = 4 * kBuf;              // two attention tiles (or hi, lo) and two Q tiles
+    // bf16 keeps hi and lo attention tiles.  Where six tiles fit the LDS (up to 24 head-branches) it runs
+    // the same single-barrier pipeline as fp16 with two hi, two lo and two Q tiles; beyond that, hi,
+    // lo and one Q tile with the phases kept apart.
+    static constexpr bool kPipeHiLo = kHiLo && 6 * kBuf <= 160 * 1024;
+    static constexpr int kTiles = (kPipeHiLo ? 6 : 4) * kBuf;
     static constexpr int kLds = kTiles;
     static_assert(kWeightStage <= kTiles, "the weights are staged through the tile area");
     static_assert(NS % 2 == 0 && TB * 16 == kThreads, "the Q tile copy takes two slabs per pass");
@@ -448,10 +452,17 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     f32x4 acc[IO][S::JT];
     const int frag_off = x16 * S::kRow + (q ^ g16) * 16;       // chunk (kk&1)*4 + q: the second half is ^ 64
     Vec bf[kRing][S::JT];
+    Vec bl[S::kPipeHiLo ? kRing : 1][S::JT];          // the lo fragments of the pipelined hi/lo form
     auto read_b = [&](int tile, int kk) {
 #pragma unroll
         for (int jt = 0; jt < S::JT; ++jt)
             bf[kk % kRing][jt] = __builtin_bit_cast(
+                Vec, *(const u32x4*)(lds + tile + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
+    };
+    auto read_b_lo = [&](int tile, int kk) {
+#pragma unroll
+        for (int jt = 0; jt < S::JT; ++jt)
+            bl[S::kPipeHiLo ? kk % kRing : 0][jt] = __builtin_bit_cast(
                 Vec, *(const u32x4*)(lds + tile + (frag_off ^ ((kk & 1) * 64)) + (kk >> 1) * S::kSlab + jt * 16 * S::kRow));
     };
     auto mma_chunk = [&](int kk) {
@@ -459,6 +470,13 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         for (int io = 0; io < IO; ++io)
 #pragma unroll
             for (int jt = 0; jt < S::JT; ++jt) acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bf[kk % kRing][jt]);
+    };
+    auto mma_chunk_lo = [&](int kk) {
+#pragma unroll
+        for (int io = 0; io < IO; ++io)
+#pragma unroll
+            for (int jt = 0; jt < S::JT; ++jt)
+                acc[io][jt] = Tr::mma_vec(acc[io][jt], wf[io][kk], bl[S::kPipeHiLo ? kk % kRing : 0][jt]);
     };
     auto zero_acc = [&]() {
 #pragma unroll
@@ -526,7 +544,8 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
     // the four tiles as byte offsets into LDS (plain numbers: a pointer chosen at run time would be
     // checked against null wherever something is added to it)
     constexpr int att0 = 0, att1 = S::kBuf, qb0 = 2 * S::kBuf, qb1 = 3 * S::kBuf;
-    if constexpr (!kHiLo) {
+    constexpr int lo0 = 4 * S::kBuf, lo1 = 5 * S::kBuf;      // (pipelined hi/lo form only)
+    if constexpr (!kHiLo || S::kPipeHiLo) {
         // prologue: Q tiles 0 and 1 parked, Q tile 2 requested, attention rows of tile 0 made
         Origin o_att = first;                 // tile whose attention rows are made next
         Origin o_q = advance(first);          // tile whose Q is requested next
@@ -543,7 +562,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
         for (int i = 0; i < S::kQV; ++i) fetch_q1(i);
         load_state(o_att.b);
         __syncthreads();
-        att_all(qb0, att0, 0);
+        att_all(qb0, att0, lo0);
         __syncthreads();
         Origin o_out = first;                 // tile whose results are written next
         o_att = advance(o_att);
@@ -551,6 +570,7 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             const bool odd = t & 1;
             const int here = odd ? att1 : att0;         // attention rows of tile t
             const int next = odd ? att0 : att1;         // ... of tile t+1, made now
+            const int here_lo = odd ? lo1 : lo0, next_lo = odd ? lo0 : lo1;
             const int q_next = odd ? qb0 : qb1;         // Q of tile t+1
             const int q_park = odd ? qb1 : qb0;         // Q of tile t+2 goes where tile t's was
             if (t + 1 < n_mine && o_att.b != img) load_state(o_att.b);
@@ -559,21 +579,29 @@ __global__ __launch_bounds__(512) void apply_project_ws_kernel(const T* __restri
             aim_out(o_out, t > 0);                      // ... and of the results of tile t-1 (none before the first)
             zero_acc();
             read_b(here, 0);
-            if constexpr (kAhead > 1) read_b(here, 1);
+            if constexpr (S::kPipeHiLo) read_b_lo(here_lo, 0);
+            if constexpr (kAhead > 1) {
+                read_b(here, 1);
+                if constexpr (S::kPipeHiLo) read_b_lo(here_lo, 1);
+            }
             att_a(q_next, 0);
             // 16 slots of IO*2 matrix instructions; everything else rides between them.  Past the
             // last tile the extra jobs work on zeros that nobody reads.
             static_for<0, KCH>([&](auto kk_c) {
                 constexpr int kk = decltype(kk_c)::value;
-                if constexpr (kk + kAhead < KCH) read_b(here, kk + kAhead);
+                if constexpr (kk + kAhead < KCH) {
+                    read_b(here, kk + kAhead);
+                    if constexpr (S::kPipeHiLo) read_b_lo(here_lo, kk + kAhead);
+                }
                 constexpr int u = kk / 2;
                 if constexpr (kk % 2 == 0) {
                     att_b(u);
                     if constexpr (u + 1 < kUnits) att_a(q_next, u + 1);
                 } else {
-                    att_c(u, next, 0);
+                    att_c(u, next, next_lo);
                 }
                 mma_chunk(kk);
+                if constexpr (S::kPipeHiLo) mma_chunk_lo(kk);
                 // Q tile t+2: registers -> LDS, then the same registers take the request for tile t+3
                 constexpr int kParkAt = 1, kFetchAt = 3;
                 if constexpr (kk >= kParkAt && kk < kParkAt + S::kQV) park_q1(q_park, kk - kParkAt);
