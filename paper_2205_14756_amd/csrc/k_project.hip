@@ -39,7 +39,7 @@ struct PlainDest {
     // rounding (y = res + x w^T); nullptr: none
     const T* res = nullptr;
     // optional activation applied to the fp32 sums before their one rounding: -1 none, 0 ReLU,
-    // 1 hard-swish a * clip(a + 3, 0, 6) / 6 (the FFN's expand projection)
+    // 1 hard-swish a * clip(a + 3, 0, 6) / 6, evaluated as a * clip(a / 6 + 1/2, 0, 1) (the FFN's expand projection)
     int act = -1;
     __host__ __device__ __forceinline__ bool has_residual() const { return res != nullptr; }
     // 16 bytes of the residual at (token, channel), zero past the ends
@@ -54,7 +54,7 @@ struct PlainDest {
             for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
         } else if (act == 1) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = v[e] * fminf(fmaxf(v[e] + 3.f, 0.f), 6.f) * (1.0f / 6.0f);
+            for (int e = 0; e < 4; ++e) v[e] = v[e] * __builtin_amdgcn_fmed3f(fmaf(v[e], 1.0f / 6.0f, 0.5f), 0.f, 1.f);
         }
         return v;
     }
@@ -384,11 +384,11 @@ __global__ __launch_bounds__(ProjTile<T>::kThreads) void project_kernel(const T*
 // multiply-add and needs no weight traffic in the loop at all.  Two such workgroups share a CU
 // (one wave of each per SIMD); they drift apart, so one's barrier and result stores are covered
 // by the other's matrix instructions.
-template <class T, int KCH>
+template <class T, int KCH, int IO_ = MSLA_WS_IO>
 struct WsShape {
     static_assert(sizeof(T) == 2 && KCH % 2 == 0, "16-bit elements, whole 128-byte slabs");
     static constexpr int kWaves = 4, kThreads = 256, kResident = MSLA_WS_RESIDENT;
-    static constexpr int IO = MSLA_WS_IO;                // 16-channel groups per wave
+    static constexpr int IO = IO_;                       // 16-channel groups per wave
     static constexpr int JT = 2;                         // 16-token groups per tile
     static constexpr int kChanWave = IO * 16, kChanBlock = kWaves * kChanWave;
     static constexpr int TB = JT * 16;                   // tokens per tile
@@ -401,11 +401,11 @@ struct WsShape {
     static_assert(TB * 8 == kThreads, "one 16-byte vector per thread and slab");
 };
 
-template <class T, int KCH, class Epilogue>
+template <class T, int KCH, int IO, class Epilogue>
 __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                          long n_tokens, int c_in, int c_out, int n_cg,
                                                          long n_tt, long tiles_per_block, Epilogue ep) {
-    typedef WsShape<T, KCH> S;
+    typedef WsShape<T, KCH, IO> S;
     typedef typename Traits<T>::Vec Vec;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -576,10 +576,10 @@ __global__ __launch_bounds__(256, MSLA_WS_RESIDENT) void project_ws_kernel(const
     for (int job = 0; job < kJobs; ++job) flush_job(job);
 }
 
-template <class T, int KCH, class Epilogue>
+template <class T, int KCH, int IO, class Epilogue>
 hipError_t run_project_ws(const void* x, const void* w, long n_tokens, int c_in, int c_out, Epilogue ep,
                           hipStream_t stream) {
-    typedef WsShape<T, KCH> S;
+    typedef WsShape<T, KCH, IO> S;
     const int n_cg = (c_out + S::kChanBlock - 1) / S::kChanBlock;
     const long n_tt = (n_tokens + S::TB - 1) / S::TB;
     if (n_tt <= 0 || n_tt * n_cg > 0x7fffffffL) return hipErrorInvalidValue;
@@ -589,9 +589,9 @@ hipError_t run_project_ws(const void* x, const void* w, long n_tokens, int c_in,
     const long groups = slots / n_cg > 0 ? slots / n_cg : 1;
     const long tiles_per_block = (n_tt + groups - 1) / groups;
     const long nblocks = (n_tt + tiles_per_block - 1) / tiles_per_block * n_cg;
-    const hipError_t e = allow_dynamic_lds<project_ws_kernel<T, KCH, Epilogue>>(S::kLds);
+    const hipError_t e = allow_dynamic_lds<project_ws_kernel<T, KCH, IO, Epilogue>>(S::kLds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((project_ws_kernel<T, KCH, Epilogue>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
+    hipLaunchKernelGGL((project_ws_kernel<T, KCH, IO, Epilogue>), dim3((unsigned)nblocks), dim3(S::kThreads), S::kLds,
                        stream, (const T*)x, (const T*)w, n_tokens, c_in, c_out, n_cg, n_tt, tiles_per_block, ep);
     return hipGetLastError();
 }
@@ -607,8 +607,14 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
         // short contraction: weights stay in registers
 #ifndef MSLA_PROJ_NO_WS
         if (!ep.has_residual()) {      // (the weight-stationary form has no residual path)
-            if (c_in <= 128) return run_project_ws<T, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
-            if (c_in <= 256) return run_project_ws<T, 8, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+            // 64 channels a wave where that divides the output (the FFN's expand projection: 1024 channels
+            // are four such workgroups instead of five and a third of the 48-channel kind), else 48
+            if (c_out % 256 == 0) {
+                if (c_in <= 128) return run_project_ws<T, 4, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+                if (c_in <= 256) return run_project_ws<T, 8, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+            }
+            if (c_in <= 128) return run_project_ws<T, 4, MSLA_WS_IO, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
+            if (c_in <= 256) return run_project_ws<T, 8, MSLA_WS_IO, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
         }
 #endif
     }
@@ -676,8 +682,8 @@ hipError_t run_qkv_project(const void* x, const void* w_qkv, void* q_ms, long q_
     if constexpr (sizeof(T) == 2 && MSLA_WS_IO == 3) {
         // weight-stationary with one head a wave
         const QkvHeadDest<T> ep{(T*)q_ms, q_ms_stride, (T*)kv_raw, kv_tok_stride, kv_head_stride, kv_span, n_tokens, heads * 16};
-        if (c_in <= 128) return run_project_ws<T, 4, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
-        if (c_in <= 256) return run_project_ws<T, 8, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
+        if (c_in <= 128) return run_project_ws<T, 4, 3, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
+        if (c_in <= 256) return run_project_ws<T, 8, 3, QkvHeadDest<T>>(x, w_qkv, n_tokens, c_in, c_out, ep, stream);
     }
 #endif
     return run_project<T>(x, w_qkv, n_tokens, c_in, c_out,

@@ -110,7 +110,9 @@ def check_module(t, dtype, heads, d, scales, eps=1e-15, options=0, stages=True):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("n,c_in,c_out", [(1000, 64, 192), (128, 256, 768), (777, 80, 48),
-                                          (300, 512, 272), (1, 16, 16), (2049, 128, 384)])
+                                          (300, 512, 272), (1, 16, 16), (2049, 128, 384),
+                                          # output channels a multiple of 256: 64 channels a wave
+                                          (1031, 256, 1024), (77, 96, 256), (2049, 128, 512)])
 def test_linear(dtype, n, c_in, c_out):
     rng = np.random.default_rng(n + c_in)
     x = wk.round_to_dtype(rng.standard_normal((n, c_in)), dtype)
@@ -122,7 +124,7 @@ def test_linear(dtype, n, c_in, c_out):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("n,c_in,c_out", [(2049, 128, 384), (1000, 256, 768), (24, 256, 768), (777, 80, 48),
-                                          (40, 512, 272)])
+                                          (40, 512, 272), (1031, 256, 1024), (77, 96, 256)])
 def test_linear_writes_only_its_own_rows(dtype, n, c_in, c_out):
     """Token counts that leave the last tile ragged: the rows behind the last token, which the same
     allocation holds, keep their contents."""
