@@ -188,6 +188,24 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
+    def graphed(fn, per_graph, replays):
+        """fn recorded per_graph times into one HIP graph on a side stream; ms per fn over `replays` replays."""
+        nonlocal stream
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        keep = stream
+        with torch.cuda.graph(g, stream=side):
+            stream = torch.cuda.current_stream()
+            for _ in range(per_graph):
+                fn()
+        stream = keep
+        for _ in range(20):
+            g.replay()
+        ms = timed(g.replay, replays)
+        del g
+        return ms / per_graph
+
     if args.state_ab:
         # The [d x N].[N x (d+1)] contraction of Eq. (3), raw branch only (no aggregated scale, so the
         # kernel does nothing else), headline shape: same launch geometry, same loads, the two ways
@@ -336,6 +354,9 @@ def main():
             others[owl.name] = {"entry": "msla_forward", "dtype": owl.dtype, "tokens": owl.tokens,
                                 "ms_per_module": round(ms, 5), "tokens_per_s": round(owl.tokens / (ms * 1e-3), 1),
                                 "module_frac": round(owl.algorithmic_bytes() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            if owl.tokens <= 8192:
+                # launch-bound: the same module recorded 20 times into one HIP graph and replayed
+                others[owl.name]["ms_per_module_in_hip_graph"] = round(graphed(o.step, 20, 100), 5)
             del o
         qkv = msla.msla_linear(r.x, r.w_qkv)
         att = torch.empty((wl.B, wl.H, wl.W, wl.branches * wl.heads * wl.head_dim), dtype=qkv.dtype, device="cuda")
@@ -406,9 +427,11 @@ def main():
         for _ in range(100):
             run_chain()
         ms = timed(run_chain, 300)
+        ms_graph = graphed(run_chain, 1, 300)
         others["block_chain_1024x2048"] = {
             "entry": "msla_block_forward x 7 (3 at 64x128 tokens C=128, 4 at 32x64 tokens C=256)", "dtype": "f16",
             "ms_per_image": round(ms, 5), "images_per_s": round(1e3 / ms, 1),
+            "ms_per_image_in_hip_graph": round(ms_graph, 5), "images_per_s_in_hip_graph": round(1e3 / ms_graph, 1),
             "context": "the paper's whole EfficientViT-B1 at this resolution: 175 images/s on an A100, TensorRT fp16 "
                        "(Table 3); another machine, another scope (whole model), not a target"}
         del chain
