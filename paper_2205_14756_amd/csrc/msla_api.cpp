@@ -64,6 +64,9 @@ msla_status check_shape(int B, int H, int W, int heads, int head_dim, const int*
         tiles = (long)((H + msla::kAggMfmaTileH - 1) / msla::kAggMfmaTileH) *
                 ((W + msla::kAggMfmaTileW - 1) / msla::kAggMfmaTileW);
         target_blocks = 256;   // one pipelined 8-wave workgroup per CU; each builds its operands once
+        // (a 3x3 and a 5x5 scale share one launch: one workgroup per CU over both halves of that grid)
+        if (n_scales == 2 && scales[0] + scales[1] == 8 && scales[0] != scales[1] && scales[0] != 1 && scales[1] != 1)
+            target_blocks = 128;
     } else {
         tiles = (N + 63) / 64;
     }
