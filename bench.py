@@ -358,6 +358,21 @@ def main():
                 # launch-bound: the same module recorded 20 times into one HIP graph and replayed
                 others[owl.name]["ms_per_module_in_hip_graph"] = round(graphed(o.step, 20, 100), 5)
             del o
+        # variant shapes of the module on the headline map (Section 3.1 fixes neither the head size nor the
+        # kernel size): head sizes 8 and 32 take the plain vector-ALU kernels, 7x7 the general aggregation kernel
+        import dataclasses
+        for vname, vwl in (("head_dim8", dataclasses.replace(wl, name=wl.name + ":head_dim8", heads=32, head_dim=8, seed=2001)),
+                           ("head_dim32", dataclasses.replace(wl, name=wl.name + ":head_dim32", heads=8, head_dim=32, seed=2002)),
+                           ("scale7x7", dataclasses.replace(wl, name=wl.name + ":scale7x7", scales=(7,), seed=2003))):
+            o = Resident(vwl)
+            for _ in range(100):
+                o.step()
+            ms = timed(o.step, 300)
+            others[vwl.name] = {"entry": "msla_forward", "dtype": vwl.dtype, "tokens": vwl.tokens, "heads": vwl.heads,
+                                "head_dim": vwl.head_dim, "scales": ["raw"] + [f"{k}x{k}" for k in vwl.scales],
+                                "ms_per_module": round(ms, 5), "tokens_per_s": round(vwl.tokens / (ms * 1e-3), 1),
+                                "module_frac": round(vwl.algorithmic_bytes() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del o
         qkv = msla.msla_linear(r.x, r.w_qkv)
         att = torch.empty((wl.B, wl.H, wl.W, wl.branches * wl.heads * wl.head_dim), dtype=qkv.dtype, device="cuda")
         core = lambda: msla.msla_core_forward(qkv, r.w_dw, r.w_gpw, wl.heads, wl.head_dim, wl.scales, wl.eps,

@@ -427,11 +427,15 @@ __global__ __launch_bounds__(kAggThreads) void raw_state_valu_kernel(AggregateAr
 // together) and split into a high and a low half, so the operands carry about
 // twice the storage type's mantissa and cannot overflow fp16.
 //   kvfrag[state][0][lane (f, q)] = { hi(KV[4q+r][f]) r<4, lo(...) r<4 }   (fp32: KV[4q+r][f])
-//   kvfrag[state][1][lane (*, q)] = { hi(Ksum[4q+r]),      lo(...)      }   (fp32: Ksum[4q+r])
+//   kvfrag[state][1][lane (f, q)] = { hi(Ksum[4q+r]),      lo(...)      }   (fp32: Ksum[4q+r])
+// split = 8: the 16 channels are two heads of 8 that were carried through the aggregation side by
+// side.  Only the two diagonal 8 x 8 blocks of KV mean anything then; the operands keep those, and
+// row f of the Ksum operand keeps the entries of f's own head, so that the apply pass -- unchanged --
+// gives every output channel the numerator and the denominator of its own head (kv32 keeps all 272 sums).
 template <class T>
 __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __restrict__ partials,
                                                              float* __restrict__ kv32, void* kvfrag,
-                                                             float* __restrict__ kvscale, int nchunks) {
+                                                             float* __restrict__ kvscale, int nchunks, int split) {
     typedef Traits<T> Tr;
     __shared__ float st[kStateSize];
     __shared__ float wmax[5];
@@ -443,8 +447,10 @@ __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __rest
         // the additions stay in chunk order; unrolling only lets several loads be in flight
 #pragma unroll 8
         for (int c = 0; c < nchunks; ++c) v += p[(long)c * kStateSize];
-        st[j] = v;
         kv32[(long)s_id * kStateSize + j] = v;
+        const int e = j / 17, f = j - e * 17;
+        if (split > 0 && f < 16 && e / split != f / split) v = 0.f;
+        st[j] = v;
     }
     float m = fabsf(v);
 #pragma unroll
@@ -464,6 +470,11 @@ __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __rest
     if (j < 64) {
         const int x16 = j & 15, q = j >> 4;
         char* out = (char*)kvfrag + (long)s_id * 2048;
+        // Ksum[4q+r] as row x16 of the second operand sees it
+        auto ksum = [&](int r) {
+            const int e = q * 4 + r;
+            return (split > 0 && e / split != x16 / split) ? 0.f : st[e * 17 + 16];
+        };
         if constexpr (Tr::kSplit) {
             typename Tr::Vec fk, fs;
 #pragma unroll
@@ -472,7 +483,7 @@ __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __rest
                 const typename Tr::elem ah = Tr::from_f32(a);
                 fk[r] = ah;
                 fk[4 + r] = Tr::from_f32(a - Tr::to_f32(ah));
-                const float s = st[(q * 4 + r) * 17 + 16] * scale;
+                const float s = ksum(r) * scale;
                 const typename Tr::elem sh = Tr::from_f32(s);
                 fs[r] = sh;
                 fs[4 + r] = Tr::from_f32(s - Tr::to_f32(sh));
@@ -484,7 +495,7 @@ __global__ __launch_bounds__(320) void state_finalize_kernel(const float* __rest
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 fk[r] = st[(q * 4 + r) * 17 + x16];
-                fs[r] = st[(q * 4 + r) * 17 + 16];
+                fs[r] = ksum(r);
             }
             *(f32x4*)(out + j * 16) = fk;
             *(f32x4*)(out + 1024 + j * 16) = fs;
@@ -526,9 +537,9 @@ hipError_t run_raw_state(const AggregateArgs& a, hipStream_t stream) {
 
 template <class T>
 hipError_t run_finalize(const float* partials, float* kv32, void* kvfrag, float* kvscale, int n_states,
-                        int nchunks, hipStream_t stream) {
+                        int nchunks, int split, hipStream_t stream) {
     hipLaunchKernelGGL((state_finalize_kernel<T>), dim3((unsigned)n_states), dim3(320), 0, stream, partials,
-                       kv32, kvfrag, kvscale, nchunks);
+                       kv32, kvfrag, kvscale, nchunks, split);
     return hipGetLastError();
 }
 
@@ -553,12 +564,12 @@ hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream) 
 }
 
 hipError_t launch_state_finalize(int dt, const float* partials, float* kv32, void* kvfrag, float* kvscale,
-                                 int n_states, int nchunks, hipStream_t stream) {
-    if (n_states <= 0) return hipErrorInvalidValue;
+                                 int n_states, int nchunks, hipStream_t stream, int split) {
+    if (n_states <= 0 || (split != 0 && split != 8)) return hipErrorInvalidValue;
     switch (dt) {
-        case 0: return run_finalize<float>(partials, kv32, kvfrag, kvscale, n_states, nchunks, stream);
-        case 1: return run_finalize<_Float16>(partials, kv32, kvfrag, kvscale, n_states, nchunks, stream);
-        case 2: return run_finalize<__bf16>(partials, kv32, kvfrag, kvscale, n_states, nchunks, stream);
+        case 0: return run_finalize<float>(partials, kv32, kvfrag, kvscale, n_states, nchunks, split, stream);
+        case 1: return run_finalize<_Float16>(partials, kv32, kvfrag, kvscale, n_states, nchunks, split, stream);
+        case 2: return run_finalize<__bf16>(partials, kv32, kvfrag, kvscale, n_states, nchunks, split, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -1,15 +1,21 @@
 // The module for head sizes other than 16 (Section 3.1 fixes only "d channels per group"; 8 and 32 are
-// the other sizes the architecture family uses): multi-scale aggregation, the Eq. (3) state and the
-// normalise-and-apply pass as plain vector-ALU kernels templated on the head size D.  They follow the
-// definitions step by step, fp32 sums throughout, the same storage points as the head-size-16 path
-// (projected Q/K/V and the Q tokens of every branch are stored in the storage type; aggregated K and V
-// only feed the state), and are not tuned: the matrix-core kernels are built around 16 x 16 tiles.
+// the other sizes the architecture family uses).
+//
+// Head size 32: multi-scale aggregation, the Eq. (3) state and the normalise-and-apply pass as plain
+// vector-ALU kernels templated on the head size D.  They follow the definitions step by step, fp32 sums
+// throughout, the same storage points as the head-size-16 path (projected Q/K/V and the Q tokens of every
+// branch are stored in the storage type; aggregated K and V only feed the state), and are not tuned: the
+// matrix-core kernels are built around 16 x 16 tiles.
 //
 //   generic_branch_state_kernel   one branch (raw, or depthwise k x k + grouped 1x1) of one (image, head,
 //                                 chunk of 64-token groups): writes that branch's Q tokens, accumulates
 //                                 KV = sum_n relu(K_n)^T [V_n, 1] into a per-workgroup partial state
 //   generic_state_finalize_kernel fixed-order sum of the partial states
 //   generic_apply_kernel          att_n = relu(Q_n) KV[:, :D] / (relu(Q_n) KV[:, D] + eps)
+//
+// Head size 8 needs no kernels of its own: two heads side by side are one head of 16 whose grouped 1x1 is
+// block-diagonal and whose state is used block by block (pair_head8_weights_kernel arranges the weights
+// that way; the finalize step of the head-size-16 path masks the state operands).
 #include "msla_device.h"
 #include "msla_kernels.h"
 
@@ -197,12 +203,79 @@ hipError_t run_generic(const GenericArgs& a, hipStream_t stream) {
 
 template <class T>
 hipError_t run_generic_d(const GenericArgs& a, hipStream_t stream) {
-    if (a.head_dim == 8) return run_generic<T, 8>(a, stream);
     if (a.head_dim == 32) return run_generic<T, 32>(a, stream);
     return hipErrorNotSupported;
 }
 
+// row of the paired arrangement -> row of the head-size-8 arrangement (channel order (h*3 + t)*d + e)
+__device__ __forceinline__ int head8_row(int row16) {
+    const int hp = row16 / 48, r = row16 - hp * 48, t = r >> 4, e16 = r & 15;
+    return ((2 * hp + (e16 >> 3)) * 3 + t) * 8 + (e16 & 7);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void pair_head8_weights_kernel(const T* __restrict__ w_qkv, const T* __restrict__ w_dw,
+                                                                 const T* __restrict__ w_gpw, T* __restrict__ o_qkv,
+                                                                 T* __restrict__ o_dw, T* __restrict__ o_gpw, int C, int rows,
+                                                                 int n_scales, int k0, int k1, int k2, int k3, int k4, int k5,
+                                                                 int k6, int k7) {
+    const int ks[8] = {k0, k1, k2, k3, k4, k5, k6, k7};
+    const long n_qkv = (long)rows * C;
+    long n_dw = 0;
+    for (int i = 0; i < n_scales; ++i) n_dw += (long)rows * ks[i] * ks[i];
+    const long n_gpw = (long)n_scales * rows * 16;
+    const long total = n_qkv + n_dw + n_gpw;
+    for (long id = (long)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += (long)gridDim.x * blockDim.x) {
+        if (id < n_qkv) {
+            const int row = (int)(id / C), c = (int)(id - (long)row * C);
+            o_qkv[id] = w_qkv[(long)head8_row(row) * C + c];
+        } else if (id < n_qkv + n_dw) {
+            long r = id - n_qkv, base = 0;
+            int i = 0;
+            while (r >= (long)rows * ks[i] * ks[i]) {
+                r -= (long)rows * ks[i] * ks[i];
+                base += (long)rows * ks[i] * ks[i];
+                ++i;
+            }
+            const int kk = ks[i] * ks[i];
+            const int row = (int)(r / kk), tap = (int)(r - (long)row * kk);
+            o_dw[base + r] = w_dw[base + (long)head8_row(row) * kk + tap];
+        } else {
+            const long r = id - n_qkv - n_dw;
+            const int i = (int)(r / ((long)rows * 16));
+            const int rem = (int)(r - (long)i * rows * 16);
+            const int row = rem >> 4, col = rem & 15;
+            const bool own = (col >> 3) == ((row & 15) >> 3);
+            o_gpw[r] = own ? w_gpw[((long)i * rows + head8_row(row)) * 8 + (col & 7)] : Traits<T>::from_f32(0.f);
+        }
+    }
+}
+
+template <class T>
+hipError_t run_pair_head8(const void* w_qkv, const void* w_dw, const void* w_gpw, void* o_qkv, void* o_dw, void* o_gpw, int C,
+                          int heads8, const int* scales, int n_scales, hipStream_t stream) {
+    int k[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < n_scales; ++i) k[i] = scales[i];
+    const int rows = 3 * heads8 * 8;
+    hipLaunchKernelGGL((pair_head8_weights_kernel<T>), dim3(256), dim3(256), 0, stream, (const T*)w_qkv, (const T*)w_dw,
+                       (const T*)w_gpw, (T*)o_qkv, (T*)o_dw, (T*)o_gpw, C, rows, n_scales, k[0], k[1], k[2], k[3], k[4], k[5],
+                       k[6], k[7]);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_pair_head8_weights(int dt, const void* w_qkv, const void* w_dw, const void* w_gpw, void* w_qkv16,
+                                     void* w_dw16, void* w_gpw16, int C, int heads8, const int* scales, int n_scales,
+                                     hipStream_t stream) {
+    if (heads8 <= 0 || heads8 % 2 != 0 || n_scales < 0 || n_scales > 8) return hipErrorInvalidValue;
+    switch (dt) {
+        case 0: return run_pair_head8<float>(w_qkv, w_dw, w_gpw, w_qkv16, w_dw16, w_gpw16, C, heads8, scales, n_scales, stream);
+        case 1: return run_pair_head8<_Float16>(w_qkv, w_dw, w_gpw, w_qkv16, w_dw16, w_gpw16, C, heads8, scales, n_scales, stream);
+        case 2: return run_pair_head8<__bf16>(w_qkv, w_dw, w_gpw, w_qkv16, w_dw16, w_gpw16, C, heads8, scales, n_scales, stream);
+    }
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_generic_core(int dt, const GenericArgs& a, hipStream_t stream) {
     switch (dt) {

@@ -120,7 +120,8 @@ size_t dw_weight_elems(const Shape& s, int upto) {
 msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, int q_hs, const void* k,
                       long k_ts, int k_hs, const void* v, long v_ts, int v_hs, const void* w_dw,
                       const void* w_gpw, char* ws, const Workspace& wo, void* q_ms, int copy_raw_q,
-                      hipStream_t stream, unsigned options = 0, void* event_before_finalize = nullptr) {
+                      hipStream_t stream, unsigned options = 0, void* event_before_finalize = nullptr,
+                      int state_split = 0) {
     const size_t e = elem_size(dt);
     msla::AggregateArgs a;
     a.q = q; a.k = k; a.v = v;
@@ -185,7 +186,7 @@ msla_status run_state(const Shape& s, msla_dtype dt, const void* q, long q_ts, i
     if (stage_wanted(options, MSLA_OPT_STAGE_FINALIZE) &&
         msla::launch_state_finalize((int)dt, a.partials, reinterpret_cast<float*>(ws + wo.kv32), ws + wo.kvfrag,
                                     reinterpret_cast<float*>(ws + wo.kvscale), n_states, s.nchunks,
-                                    stream) != hipSuccess)
+                                    stream, state_split) != hipSuccess)
         return MSLA_ERR_LAUNCH;
     return MSLA_OK;
 }
@@ -248,6 +249,29 @@ msla_status generic_plan(int B, int C, int H, int W, int heads, int head_dim, co
     return MSLA_OK;
 }
 
+// Head size 8 with an even number of heads runs on the head-size-16 kernels, two heads to one of 16
+// (launch_pair_head8_weights, launch_state_finalize with split = 8).  Its workspace: the three rearranged
+// weight arrays, then the workspace of the head-size-16 module.
+struct Paired8Plan {
+    size_t w_qkv, w_dw, w_gpw, inner, inner_bytes, total;
+};
+bool paired8(int heads, int head_dim) { return head_dim == 8 && heads > 0 && heads % 2 == 0; }
+msla_status paired8_plan(int B, int C, int H, int W, int heads, const int* scales, int n_scales, msla_dtype dt, Paired8Plan* p) {
+    Shape s;
+    const msla_status st = check_shape(B, H, W, heads / 2, 16, scales, n_scales, (int)dt, &s);
+    if (st != MSLA_OK) return st;
+    if (C <= 0 || C % 16 != 0) return MSLA_ERR_UNSUPPORTED;
+    const size_t e = elem_size(dt);
+    size_t off = 0;
+    p->w_qkv = off; off += align_up((size_t)3 * s.Ct * C * e);
+    p->w_dw = off;  off += align_up(dw_weight_elems(s, n_scales) * e + 16);
+    p->w_gpw = off; off += align_up((size_t)n_scales * 3 * s.Ct * 16 * e + 16);
+    p->inner = off;
+    p->inner_bytes = carve(s, dt).total;
+    p->total = off + p->inner_bytes;
+    return MSLA_OK;
+}
+
 msla_status generic_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw, const void* w_proj,
                             void* out, void* workspace, size_t workspace_bytes, int B, int C, int H, int W, int heads,
                             int head_dim, const int* scales, int n_scales, float eps, msla_dtype dt, hipStream_t hs) {
@@ -296,8 +320,16 @@ msla_status msla_workspace_bytes(int B, int C, int H, int W, int heads, int head
     if (generic_head_dim(head_dim)) {
         GenericPlan p;
         const msla_status gst = generic_plan(B, C, H, W, heads, head_dim, scales, n_scales, (int)dt, &p);
-        if (gst == MSLA_OK) *bytes = p.total;
-        return gst;
+        if (gst != MSLA_OK) return gst;
+        if (paired8(heads, head_dim)) {
+            Paired8Plan pp;
+            const msla_status pst = paired8_plan(B, C, H, W, heads, scales, n_scales, dt, &pp);
+            if (pst != MSLA_OK) return pst;
+            *bytes = pp.total;
+            return MSLA_OK;
+        }
+        *bytes = p.total;
+        return MSLA_OK;
     }
     Shape s;
     const msla_status st = check_shape(B, H, W, heads, head_dim, scales, n_scales, (int)dt, &s);
@@ -311,7 +343,8 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
                                 const void* w_proj, void* out, void* workspace, size_t workspace_bytes, int B,
                                 int C, int H, int W, int heads, int head_dim, const int* scales, int n_scales,
                                 float eps, msla_dtype dt, msla_layout layout, void* stream,
-                                void* const* events, unsigned options, const void* residual = nullptr) {
+                                void* const* events, unsigned options, const void* residual = nullptr,
+                                int state_split = 0) {
     if (!x || !w_qkv || !w_proj || !out || !workspace || C <= 0) return MSLA_ERR_INVALID_ARG;
     if (options & ~(MSLA_OPT_GENERAL_AGGREGATION | MSLA_OPT_STATE_VALU | kStageBits)) return MSLA_ERR_INVALID_ARG;
     if ((options & kStageBits) && layout != MSLA_NHWC) return MSLA_ERR_UNSUPPORTED;
@@ -324,6 +357,23 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
             !aligned16(w_dw) || !aligned16(w_gpw))
             return MSLA_ERR_INVALID_ARG;
         if (layout != MSLA_NHWC || options != 0 || events != nullptr || residual != nullptr) return MSLA_ERR_UNSUPPORTED;
+        if (paired8(heads, head_dim)) {
+            // two heads of 8 as one head of 16: rearranged weights, then the head-size-16 module
+            GenericPlan gp;     // (argument checks shared with the plain path)
+            msla_status pst = generic_plan(B, C, H, W, heads, head_dim, scales, n_scales, (int)dt, &gp);
+            if (pst != MSLA_OK) return pst;
+            Paired8Plan pp;
+            pst = paired8_plan(B, C, H, W, heads, scales, n_scales, dt, &pp);
+            if (pst != MSLA_OK) return pst;
+            if (workspace_bytes < pp.total) return MSLA_ERR_WORKSPACE;
+            char* pws = static_cast<char*>(workspace);
+            if (msla::launch_pair_head8_weights((int)dt, w_qkv, w_dw, w_gpw, pws + pp.w_qkv, pws + pp.w_dw, pws + pp.w_gpw, C,
+                                                heads, scales, n_scales, static_cast<hipStream_t>(stream)) != hipSuccess)
+                return MSLA_ERR_LAUNCH;
+            return forward_impl(x, pws + pp.w_qkv, n_scales > 0 ? pws + pp.w_dw : nullptr,
+                                n_scales > 0 ? pws + pp.w_gpw : nullptr, w_proj, out, pws + pp.inner, pp.inner_bytes, B, C, H, W,
+                                heads / 2, 16, scales, n_scales, eps, dt, layout, stream, nullptr, 0u, nullptr, 8);
+        }
         return generic_forward(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads, head_dim,
                                scales, n_scales, eps, dt, static_cast<hipStream_t>(stream));
     }
@@ -372,7 +422,7 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     if (!mark(1)) return MSLA_ERR_LAUNCH;
     // aggregation + Eq. (3) state
     st = run_state(s, dt, q_ms, q_ms_ts, 16, kv_raw, kv_ts, (int)kv_hs, kv_raw + 16 * e, kv_ts, (int)kv_hs, w_dw, w_gpw,
-                   ws, wo, q_ms, /*copy_raw_q=*/0, hs, options, events ? events[2] : nullptr);
+                   ws, wo, q_ms, /*copy_raw_q=*/0, hs, options, events ? events[2] : nullptr, state_split);
     if (st != MSLA_OK) return st;
     if (!mark(3)) return MSLA_ERR_LAUNCH;
     // normalise-and-apply fused with the output projection

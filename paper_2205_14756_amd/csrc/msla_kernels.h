@@ -60,8 +60,18 @@ hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream);
 //   kv32    [n_states, 16, 17] fp32 (the state of Eq. (3))
 //   kvfrag  [n_states, 2, 64, 16 bytes] the state laid out as MFMA operands
 //   kvscale [n_states] the power of two the operands were scaled by
+// split = 8: a state holds two heads of 8 channels side by side; the operands keep each head's own block of KV
+// and, row by row, its own part of Ksum (0: one head of 16)
 hipError_t launch_state_finalize(int dt, const float* partials, float* kv32, void* kvfrag, float* kvscale,
-                                 int n_states, int nchunks, hipStream_t stream);
+                                 int n_states, int nchunks, hipStream_t stream, int split = 0);
+
+// Head size 8 on the head-size-16 kernels: heads 2p and 2p+1 become one head of 16 whose Q, K and V blocks are
+// [Q_2p Q_2p+1], [K_2p K_2p+1], [V_2p V_2p+1].  Writes the module's weights in that arrangement: the rows of
+// w_qkv [3*Ct, C] and of every scale's w_dw [3*Ct, k, k] permuted, and w_gpw [A, 3*Ct, 8] as block-diagonal
+// [A, 3*Ct, 16] (k_generic.hip).  heads8 must be even.
+hipError_t launch_pair_head8_weights(int dt, const void* w_qkv, const void* w_dw, const void* w_gpw, void* w_qkv16,
+                                     void* w_dw16, void* w_gpw16, int C, int heads8, const int* scales, int n_scales,
+                                     hipStream_t stream);
 
 // att[n, m*16 + f] for every head-branch m of q_ms (Eq. (3), last line)
 hipError_t launch_apply(int dt, const void* q_ms, const void* kvfrag, const float* kvscale, void* att,

@@ -28,6 +28,22 @@ The number of listed tokens is checked against a CPU prediction: the oracle's
 own stage functions composed with the storage rounding (``storage_reading``).
 THETA is not tuned on the GPU: ``tests/test_parity_model.py`` shows on the CPU
 that every token the storage reading moves past the bar has a margin below it.
+
+That holds for the benchmark workloads (heads of 16 channels).  With heads of 8
+channels and bf16 storage a gate has half as many terms, and the CPU's storage
+reading alone moves tokens whose margins are a few THETA past the bar: not a
+flip between hull vertices, but the first-order effect of one rounding of Q,
+(2u / margin) times the spread of the hull, which the projection carries into
+the output.  A token over the bar is therefore also accepted when
+
+  (iii) that first-order bound for one of its head-branches
+        (``first_order_bound``, in units of max|out|, computed from the plain
+        oracle alone) is at least the bar, AND the output is within the bar of
+        the CPU's storage reading at that token.
+
+(iii) takes no value from the GPU either, cannot excuse a well-conditioned
+token, and still pins the GPU's value to within the bar of a CPU-computed one.
+The count check covers the tokens of (i)-(ii) and of (iii) together.
 """
 from __future__ import annotations
 
@@ -142,6 +158,29 @@ def token_validity(out_row, plain_out_row, plain_att_row, w_proj, states, ill, d
     return float(best)
 
 
+def first_order_bound(att_row, w_proj, kv_b, margin_row, heads, d, u, scale):
+    """What the storage rounding of Q can do to one output token through ONE head-branch, to first order,
+    in units of `scale`: the largest over the head-branches m of
+    (2u / margin_m) * max_e |W_proj[:, m] (KV[e,:]/Ksum[e] - att_m)|_inf
+    -- perturbations of size u|Q| move the denominator of Eq. (3) by u / margin of itself, and the row by that
+    fraction of the way to a hull vertex.  kv_b [S, heads, d, d+1] are the states of the token's image;
+    inf where a margin is 0."""
+    worst = 0.0
+    for m in range(margin_row.shape[0]):
+        state = kv_b[m // heads, m % heads]
+        rows = hull_rows(state)
+        if rows.shape[0] == 0:
+            continue
+        cols = slice(m * d, (m + 1) * d)
+        spread = np.abs(w_proj[:, cols] @ (rows - att_row[cols]).T).max()
+        if spread <= 0:
+            continue
+        if margin_row[m] <= 0:
+            return np.inf
+        worst = max(worst, 2.0 * u / margin_row[m] * spread / scale)
+    return float(worst)
+
+
 class Judgement:
     """Outcome of judge_module / judge_core, printable."""
 
@@ -157,12 +196,13 @@ class Judgement:
         return s
 
 
-def predicted_tokens(t, dtype, heads, d, scales, eps, plain_out):
+def predicted_tokens(t, dtype, heads, d, scales, eps, plain_out, return_reading=False):
     """Tokens that the storage reading (CPU only) moves past the bar."""
     out_s, _ = storage_reading(t, dtype, heads, d, scales, eps)
     out_s = wk.round_to_dtype(out_s, dtype)
     err = np.abs(out_s - plain_out).max(-1) / np.abs(plain_out).max()
-    return [tuple(int(i) for i in idx) for idx in np.argwhere(err > TOL[dtype])]
+    toks = [tuple(int(i) for i in idx) for idx in np.argwhere(err > TOL[dtype])]
+    return (toks, out_s) if return_reading else toks
 
 
 def judge_module(got, t, dtype, heads, d, scales, eps, slack: int = 0) -> Judgement:
@@ -177,9 +217,8 @@ def judge_module(got, t, dtype, heads, d, scales, eps, slack: int = 0) -> Judgem
     err = np.abs(got - plain).max(-1) / scale                          # [B,H,W]
     margin = gate_margin(parts["q_tokens"], parts["kv"], heads, d)     # [B,H,W,S*heads]
     over = [tuple(int(i) for i in idx) for idx in np.argwhere(err > tol)]
-    predicted = predicted_tokens(t, dtype, heads, d, scales, eps, plain)
+    predicted, reading = predicted_tokens(t, dtype, heads, d, scales, eps, plain, return_reading=True)
     listed, problems = [], []
-    S = parts["kv"].shape[1]
     for tok in over:
         b = tok[0]
         ill = [int(m) for m in np.nonzero(margin[tok] < theta(dtype))[0]]
@@ -187,10 +226,22 @@ def judge_module(got, t, dtype, heads, d, scales, eps, slack: int = 0) -> Judgem
         dist = (token_validity(got[tok], plain[tok], parts["att"][tok], t["w_proj"], states, ill, d, scale) / scale
                 if ill and len(ill) <= 4 else np.inf)
         listed.append((tok, float(err[tok]), float(margin[tok].min()), dist))
-        if not ill:
-            problems.append(f"token {tok}: err {err[tok]:.3e} with a well-conditioned gate (margin {margin[tok].min():.3e})")
-        elif dist > tol:
-            problems.append(f"token {tok}: err {err[tok]:.3e}, not an admissible value of Eq. (3) (distance {dist:.3e})")
+        if ill and dist <= tol:
+            continue                                    # (i) + (ii)
+        bound = first_order_bound(parts["att"][tok], t["w_proj"], parts["kv"][b], margin[tok], heads, d,
+                                  UNIT_ROUNDOFF[dtype], scale)
+        off_reading = float(np.abs(got[tok] - reading[tok]).max() / scale)
+        if bound >= tol and off_reading <= tol:
+            continue                                    # (iii)
+        if not ill and bound < tol:
+            problems.append(f"token {tok}: err {err[tok]:.3e} with a well-conditioned gate (margin {margin[tok].min():.3e}, "
+                            f"first-order bound {bound:.3e})")
+        elif bound >= tol and not ill:
+            problems.append(f"token {tok}: err {err[tok]:.3e}, ill-conditioned to first order (bound {bound:.3e}) but "
+                            f"{off_reading:.3e} away from the storage reading")
+        else:
+            problems.append(f"token {tok}: err {err[tok]:.3e}, not an admissible value of Eq. (3) (distance {dist:.3e}; "
+                            f"{off_reading:.3e} away from the storage reading)")
     ok = np.ones(err.shape, dtype=bool)
     for tok in over:
         ok[tok] = False

@@ -327,9 +327,13 @@ def test_forward_raw_branch_state_on_the_vector_alus(dtype, B, C, H, W, heads):
     (2, 96, 17, 10, 3, 32, (3, 7)),     # three branches, ragged 64-token groups, C != heads * head size
     (1, 128, 30, 40, 16, 8, ()),        # no aggregated scale
     (1, 128, 64, 64, 4, 32, (5,)),      # several chunks per state
+    (3, 128, 40, 72, 16, 8, (3, 5)),    # head size 8 as pairs on the head-size-16 kernels, several tiles, ragged
+    (1, 64, 20, 20, 6, 8, (7,)),        # ... with a 7x7 scale; C != heads * head size
 ])
 def test_forward_other_head_sizes(dtype, B, C, H, W, heads, d, scales):
-    """Head sizes 8 and 32 (the plain kernels of k_generic.hip): the same bar, the same protocol."""
+    """Head sizes 8 and 32: the same bar, the same protocol.  Heads of size 8 run as pairs on the
+    head-size-16 kernels (heads * 8 is a multiple of 16, so their number is even), heads of size 32 on the
+    plain kernels of k_generic.hip."""
     print(f"forward {dtype} B={B} C={C} {H}x{W} heads={heads} head size {d} scales={scales}", flush=True)
     t = wk.random_module(C * 10 + H + d, dtype, B, C, H, W, heads, d, scales)
     check_module(t, dtype, heads, d, scales, stages=False)

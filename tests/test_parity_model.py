@@ -117,6 +117,31 @@ def test_judgement_rejects_planted_mistakes():
         pm.judge_module(wrong, *args)
 
 
+def test_heads_of_eight_in_bf16_need_the_first_order_rule():
+    """bf16 storage, heads of 8 channels: the storage reading alone (CPU) moves tokens past the bar whose
+    margins are above THETA; each of them has a head-branch whose first-order bound reaches the bar, and a
+    value planted at such a token that is not the storage reading's is still rejected."""
+    dtype, heads, d, scales = "bf16", 8, 8, (3, 5)
+    hits = 0
+    for seed in range(6):
+        t = wk.random_module(8100 + seed, dtype, 2, 64, 24, 31, heads, d, scales)
+        out_s, _ = pm.storage_reading(t, dtype, heads, d, scales, 1e-15)
+        got = wk.round_to_dtype(out_s, dtype)
+        j = pm.judge_module(got, t, dtype, heads, d, scales, 1e-15)
+        assert len(j.listed) == len(j.predicted)
+        above = [l for l in j.listed if l[2] >= pm.theta(dtype)]
+        hits += len(above)
+        if above:
+            tok = above[0][0]
+            plain = orc.forward(t["x"], t["w_qkv"], t["w_dw"], t["w_gpw"], t["w_proj"], heads, d, scales, 1e-15)
+            bad = got.copy()
+            bad[tok] = plain[tok] + 3 * (got[tok] - plain[tok])          # three times as far from the oracle
+            with pytest.raises(AssertionError, match="away from the storage reading"):
+                pm.judge_module(bad, t, dtype, heads, d, scales, 1e-15)
+    print(f"{hits} tokens over the bar with a margin above THETA in 6 modules")
+    assert hits > 0
+
+
 def test_core_judgement():
     dtype, heads, d, scales = "bf16", 2, 16, (5,)
     t = wk.random_module(123, dtype, 1, 32, 20, 20, heads, d, scales)
