@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmsla.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["k_project.hip", "k_aggregate.hip", "k_aggregate_mfma.hip", "k_apply.hip", "k_small.hip", "k_ffn.hip", "k_softmax.hip", "k_backward.hip", "k_generic.hip", "k_layout.hip", "msla_static.hip", "msla_api.cpp"]
+SOURCES = ["k_project.hip", "k_aggregate.hip", "k_aggregate_mfma.hip", "k_aggregate32.hip", "k_apply.hip", "k_small.hip", "k_ffn.hip", "k_softmax.hip", "k_backward.hip", "k_generic.hip", "k_layout.hip", "msla_static.hip", "msla_api.cpp"]
 HEADERS = ["msla_device.h", "gemm_tile.h", "msla_kernels.h", os.path.join("..", "..", "include", "msla.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -16,6 +16,8 @@
 // Head size 8 needs no kernels of its own: two heads side by side are one head of 16 whose grouped 1x1 is
 // block-diagonal and whose state is used block by block (pair_head8_weights_kernel arranges the weights
 // that way; the finalize step of the head-size-16 path masks the state operands).
+#include <type_traits>
+
 #include "msla_device.h"
 #include "msla_kernels.h"
 
@@ -138,56 +140,77 @@ __global__ __launch_bounds__(kGenThreads) void generic_state_finalize_kernel(con
     }
 }
 
-// one workgroup = 256 tokens of one (image, head-branch m): a thread per token
+// one workgroup = 256 tokens of one (image, head-branch m): a thread per token.  The state sits in LDS with
+// its rows padded to a multiple of four floats, so that a row is read four values at a time (every lane reads
+// the same address: a broadcast); a token's Q row comes in and its attention row goes out as 16-byte vectors.
 template <class T, int D>
 __global__ __launch_bounds__(kGenThreads) void generic_apply_kernel(const T* __restrict__ q_ms, const float* __restrict__ kv32,
                                                                     T* __restrict__ att, int N, int n_hb, int blocks_per_image,
                                                                     float eps) {
     constexpr int kState = D * (D + 1);
-    __shared__ float St[kState];
+    constexpr int kRow = D + 4;                     // padded row: KV[e][0..D-1], Ksum[e], 3 unused
+    constexpr int kVecElems = 16 / (int)sizeof(T);  // elements per 16-byte vector
+    static_assert(D % 8 == 0, "whole vectors");
+    __shared__ __attribute__((aligned(16))) float St[D * kRow];
     const int m = blockIdx.x % n_hb;
     const int nb = (blockIdx.x / n_hb) % blocks_per_image;
     const int b = blockIdx.x / (n_hb * blocks_per_image);
-    for (int j = threadIdx.x; j < kState; j += kGenThreads) St[j] = kv32[((long)b * n_hb + m) * kState + j];
+    for (int j = threadIdx.x; j < kState; j += kGenThreads) {
+        const int e = j / (D + 1), f = j - e * (D + 1);
+        St[e * kRow + f] = kv32[((long)b * n_hb + m) * kState + j];
+    }
     __syncthreads();
     const int n = nb * kGenThreads + threadIdx.x;
     if (n >= N) return;
     const long row = ((long)b * N + n) * ((long)n_hb * D) + (long)m * D;
+    float rq[D];
+#pragma unroll
+    for (int v = 0; v < D / kVecElems; ++v) {
+        const u32x4 raw = *(const u32x4*)(q_ms + row + v * kVecElems);
+        if constexpr (sizeof(T) == 4) {
+            const f32x4 x = __builtin_bit_cast(f32x4, raw);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rq[v * 4 + i] = fmaxf(x[i], 0.f);
+        } else {
+            const typename Traits<T>::Vec x = __builtin_bit_cast(typename Traits<T>::Vec, raw);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rq[v * 8 + i] = fmaxf(Traits<T>::to_f32(x[i]), 0.f);
+        }
+    }
     float num[D];
 #pragma unroll
     for (int f = 0; f < D; ++f) num[f] = 0.f;
     float den = eps;
 #pragma unroll
     for (int e = 0; e < D; ++e) {
-        const float rq = fmaxf(Traits<T>::to_f32(q_ms[row + e]), 0.f);
-        den = fmaf(rq, St[e * (D + 1) + D], den);
+        den = fmaf(rq[e], St[e * kRow + D], den);
 #pragma unroll
-        for (int f = 0; f < D; ++f) num[f] = fmaf(rq, St[e * (D + 1) + f], num[f]);
+        for (int f4 = 0; f4 < D; f4 += 4) {
+            const f32x4 s4 = *(const f32x4*)(St + e * kRow + f4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) num[f4 + i] = fmaf(rq[e], s4[i], num[f4 + i]);
+        }
     }
     const float inv = 1.0f / den;
 #pragma unroll
-    for (int f = 0; f < D; ++f) att[row + f] = Traits<T>::from_f32(num[f] * inv);
+    for (int v = 0; v < D / kVecElems; ++v) {
+        u32x4 raw;
+        if constexpr (sizeof(T) == 4) {
+            raw = __builtin_bit_cast(u32x4, f32x4{num[v * 4] * inv, num[v * 4 + 1] * inv, num[v * 4 + 2] * inv, num[v * 4 + 3] * inv});
+        } else {
+            typename Traits<T>::Vec x;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = Traits<T>::from_f32(num[v * 8 + i] * inv);
+            raw = __builtin_bit_cast(u32x4, x);
+        }
+        *(u32x4*)(att + row + v * kVecElems) = raw;
+    }
 }
 
+// fixed-order sum of the partial states, then the normalise-and-apply pass
 template <class T, int D>
-hipError_t run_generic(const GenericArgs& a, hipStream_t stream) {
-    const int N = a.H * a.W;
-    const int n_groups = (N + kGenTokens - 1) / kGenTokens;
-    const int gpc = (n_groups + a.nchunks - 1) / a.nchunks;
-    const long nb = (long)a.B * a.heads * a.nchunks;
-    if (nb <= 0 || nb > 0x7fffffffL) return hipErrorInvalidValue;
+hipError_t finish_generic(const GenericArgs& a, int N, hipStream_t stream) {
     const int S = 1 + a.n_scales;
-    size_t dw_off = 0;
-    for (int s = 0; s < S; ++s) {
-        const int ks = s == 0 ? 0 : a.scales[s - 1];
-        const T* wdw = s == 0 ? nullptr : (const T*)a.w_dw + dw_off;
-        const T* wgp = s == 0 ? nullptr : (const T*)a.w_gpw + (size_t)(s - 1) * 3 * a.heads * D * D;
-        if (s > 0) dw_off += (size_t)3 * a.heads * D * ks * ks;
-        hipLaunchKernelGGL((generic_branch_state_kernel<T, D>), dim3((unsigned)nb), dim3(kGenThreads), 0, stream,
-                           (const T*)a.qkv, wdw, wgp, (T*)a.q_ms, a.partials, a.H, a.W, a.heads, S, s, ks, a.nchunks, gpc);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
     const int n_states = a.B * S * a.heads;
     hipLaunchKernelGGL((generic_state_finalize_kernel<D>), dim3((unsigned)n_states), dim3(kGenThreads), 0, stream, a.partials,
                        a.kv32, a.nchunks);
@@ -199,6 +222,59 @@ hipError_t run_generic(const GenericArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL((generic_apply_kernel<T, D>), dim3((unsigned)nb2), dim3(kGenThreads), 0, stream, (const T*)a.q_ms, a.kv32,
                        (T*)a.att, N, S * a.heads, bpi, a.eps);
     return hipGetLastError();
+}
+
+template <class T, int D>
+hipError_t run_generic(const GenericArgs& a, hipStream_t stream) {
+    const int N = a.H * a.W;
+    const int n_groups = (N + kGenTokens - 1) / kGenTokens;
+    const int gpc = (n_groups + a.nchunks - 1) / a.nchunks;
+    const long nb = (long)a.B * a.heads * a.nchunks;
+    if (nb <= 0 || nb > 0x7fffffffL) return hipErrorInvalidValue;
+    const int S = 1 + a.n_scales;
+    size_t dw_off = 0;
+    if constexpr (D == 32 && sizeof(T) == 2) {
+        if (a.n_scales > 0) {
+            // 16-bit storage: the tiled matrix-core form (k_aggregate32.hip); its first launch also does the
+            // raw branch.  Same partial-state buffer, chunks counted in 8 x 32-token tiles.
+            AggregateArgs g;
+            g.q = a.qkv;
+            g.k = (const T*)a.qkv + D;
+            g.v = (const T*)a.qkv + 2 * D;
+            g.q_ts = g.k_ts = g.v_ts = 3L * a.heads * D;
+            g.q_hs = g.k_hs = g.v_hs = 3 * D;
+            g.q_ms = a.q_ms;
+            g.partials = a.partials;
+            g.B = a.B; g.H = a.H; g.W = a.W; g.heads = a.heads; g.S = S;
+            g.nchunks = a.nchunks;
+            const long tiles = (long)((a.H + kAggTileH - 1) / kAggTileH) * ((a.W + kAggTileW - 1) / kAggTileW);
+            g.tiles_per_chunk = (int)((tiles + a.nchunks - 1) / a.nchunks);
+            for (int i = 0; i < a.n_scales; ++i) {
+                const int ks = a.scales[i];
+                g.w_dw = (const T*)a.w_dw + dw_off;
+                g.w_gpw = (const T*)a.w_gpw + (size_t)i * 3 * a.heads * D * D;
+                dw_off += (size_t)3 * a.heads * D * ks * ks;
+                g.ks = ks;
+                g.branch = i + 1;
+                g.do_raw = (i == 0);
+                g.copy_raw_q = (i == 0);
+                const hipError_t e = launch_aggregate32(sizeof(T) == 2 && std::is_same<T, _Float16>::value ? 1 : 2, g, stream);
+                if (e != hipSuccess) return e;
+            }
+            return finish_generic<T, D>(a, N, stream);
+        }
+    }
+    for (int s = 0; s < S; ++s) {
+        const int ks = s == 0 ? 0 : a.scales[s - 1];
+        const T* wdw = s == 0 ? nullptr : (const T*)a.w_dw + dw_off;
+        const T* wgp = s == 0 ? nullptr : (const T*)a.w_gpw + (size_t)(s - 1) * 3 * a.heads * D * D;
+        if (s > 0) dw_off += (size_t)3 * a.heads * D * ks * ks;
+        hipLaunchKernelGGL((generic_branch_state_kernel<T, D>), dim3((unsigned)nb), dim3(kGenThreads), 0, stream,
+                           (const T*)a.qkv, wdw, wgp, (T*)a.q_ms, a.partials, a.H, a.W, a.heads, S, s, ks, a.nchunks, gpc);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return finish_generic<T, D>(a, N, stream);
 }
 
 template <class T>

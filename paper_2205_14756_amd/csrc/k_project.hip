@@ -607,9 +607,10 @@ hipError_t run_project(const void* x, const void* w, long n_tokens, int c_in, in
         // short contraction: weights stay in registers
 #ifndef MSLA_PROJ_NO_WS
         if (!ep.has_residual()) {      // (the weight-stationary form has no residual path)
-            // 64 channels a wave where that divides the output (the FFN's expand projection: 1024 channels
-            // are four such workgroups instead of five and a third of the 48-channel kind), else 48
-            if (c_out % 256 == 0) {
+            // 64 channels a wave where that divides the output and 48 does not (the FFN's expand projection:
+            // 1024 channels are four such workgroups instead of five and a third of the 48-channel kind;
+            // 42 against 57 us there, 24 against 31 at 512 channels, but 39.5 against 37 at 768), else 48
+            if (c_out % 256 == 0 && c_out % 192 != 0) {
                 if (c_in <= 128) return run_project_ws<T, 4, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
                 if (c_in <= 256) return run_project_ws<T, 8, 4, Epilogue>(x, w, n_tokens, c_in, c_out, ep, stream);
             }

@@ -53,6 +53,10 @@ hipError_t launch_aggregate_mfma(int dt, const AggregateArgs& a, hipStream_t str
 // without launching, for anything else (then the caller launches them one by one).
 hipError_t launch_aggregate_mfma_pair(int dt, const AggregateArgs& a0, const AggregateArgs& a1, hipStream_t stream);
 
+// The same contract for heads of 32 channels, fp16 / bf16 (k_aggregate32.hip): maps with 32 channels per head and
+// kind, w_gpw rows of 32, partial states [.., nchunks, 32*33], 8 x 32-token tiles.  hipErrorNotSupported for fp32.
+hipError_t launch_aggregate32(int dt, const AggregateArgs& a, hipStream_t stream);
+
 // Raw-branch-only variant for n_scales == 0 (no convolution): state of branch 0, optional Q copy.
 hipError_t launch_raw_state(int dt, const AggregateArgs& a, hipStream_t stream);
 
