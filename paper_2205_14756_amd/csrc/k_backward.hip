@@ -18,6 +18,12 @@ namespace msla {
 namespace {
 
 constexpr int kBwdThreads = 256;
+// a state in LDS: rows padded from 17 to 20 floats, so that four columns are one 16-byte read
+constexpr int kRowS = 20;
+constexpr int kLdsState = 16 * kRowS;
+__device__ __forceinline__ void stage_state(float* dst, const float* __restrict__ src, int tid, int nthreads) {
+    for (int j = tid; j < kStateSize; j += nthreads) dst[(j / 17) * kRowS + j % 17] = src[j];
+}
 
 // What both kernels need of one token: its rectified query, and from S and dA the quantities g
 // (this lane's four columns) and c.
@@ -38,7 +44,7 @@ __device__ __forceinline__ void load16(const T* p, float (&f)[16]) {
     }
 }
 
-// S: this (image, head)'s forward state in LDS, [16][17].  live: the token exists.
+// S: this (image, head)'s forward state in LDS, [16][kRowS].  live: the token exists.
 template <class T>
 __device__ __forceinline__ TokenGrad<T> token_grad(const T* q_tok, const T* da_tok, const float* S, int p, float eps,
                                                    bool live) {
@@ -56,9 +62,10 @@ __device__ __forceinline__ TokenGrad<T> token_grad(const T* q_tok, const T* da_t
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         t.rq[e] = fmaxf(q[e], 0.f);
-        den = fmaf(t.rq[e], S[e * 17 + 16], den);
+        den = fmaf(t.rq[e], S[e * kRowS + 16], den);
+        const f32x4 s4 = *(const f32x4*)(S + e * kRowS + p * 4);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) num[j] = fmaf(t.rq[e], S[e * 17 + p * 4 + j], num[j]);
+        for (int j = 0; j < 4; ++j) num[j] = fmaf(t.rq[e], s4[j], num[j]);
     }
     const float inv = live ? 1.0f / den : 0.f;
     float dot = 0.f;
@@ -79,14 +86,14 @@ __global__ __launch_bounds__(kBwdThreads) void backward_state_kernel(const T* __
                                                                      const float* __restrict__ kv32,
                                                                      float* __restrict__ partials, int N, int heads,
                                                                      int nchunks, int groups_per_chunk, float eps) {
-    __shared__ float S[kStateSize];
+    __shared__ __attribute__((aligned(16))) float S[kLdsState];
     __shared__ float red[4 * kStateSize];
     const int h = blockIdx.x % heads;
     const int chunk = (blockIdx.x / heads) % nchunks;
     const int b = blockIdx.x / (heads * nchunks);
     const int lane = lane_id(), wave = threadIdx.x >> 6, slot = lane >> 2, p = lane & 3;
     const long sid = (long)b * heads + h;
-    for (int j = threadIdx.x; j < kStateSize; j += kBwdThreads) S[j] = kv32[sid * kStateSize + j];
+    stage_state(S, kv32 + sid * kStateSize, threadIdx.x, kBwdThreads);
     __syncthreads();
     const long ts = 3L * heads * 16;
     float acc[16][4], accs[16];
@@ -140,17 +147,15 @@ __global__ __launch_bounds__(kBwdThreads) void backward_apply_kernel(const T* __
                                                                      const float* __restrict__ kv32,
                                                                      const float* __restrict__ ds32, T* __restrict__ d_qkv,
                                                                      int N, int heads, int blocks_per_image, float eps) {
-    __shared__ float S[kStateSize];
-    __shared__ float dS[kStateSize];
+    __shared__ __attribute__((aligned(16))) float S[kLdsState];
+    __shared__ __attribute__((aligned(16))) float dS[kLdsState];
     const int h = blockIdx.x % heads;
     const int nb = (blockIdx.x / heads) % blocks_per_image;
     const int b = blockIdx.x / (heads * blocks_per_image);
     const int lane = lane_id(), wave = threadIdx.x >> 6, slot = lane >> 2, p = lane & 3;
     const long sid = (long)b * heads + h;
-    for (int j = threadIdx.x; j < kStateSize; j += kBwdThreads) {
-        S[j] = kv32[sid * kStateSize + j];
-        dS[j] = ds32[sid * kStateSize + j];
-    }
+    stage_state(S, kv32 + sid * kStateSize, threadIdx.x, kBwdThreads);
+    stage_state(dS, ds32 + sid * kStateSize, threadIdx.x, kBwdThreads);
     __syncthreads();
     const long ts = 3L * heads * 16;
     const long n = (long)nb * 64 + wave * 16 + slot;
@@ -176,12 +181,17 @@ __global__ __launch_bounds__(kBwdThreads) void backward_apply_kernel(const T* __
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = p * 4 + i;
-        float a = S[e * 17 + 16] * t.c;
-        float bk = dS[e * 17 + 16];
+        float a = S[e * kRowS + 16] * t.c;
+        float bk = dS[e * kRowS + 16];
 #pragma unroll
-        for (int f = 0; f < 16; ++f) {
-            a = fmaf(S[e * 17 + f], g_all[f], a);
-            bk = fmaf(dS[e * 17 + f], v[f], bk);
+        for (int f4 = 0; f4 < 16; f4 += 4) {
+            const f32x4 s4 = *(const f32x4*)(S + e * kRowS + f4);
+            const f32x4 d4 = *(const f32x4*)(dS + e * kRowS + f4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                a = fmaf(s4[j], g_all[f4 + j], a);
+                bk = fmaf(d4[j], v[f4 + j], bk);
+            }
         }
         // (a lane's own Q and K entries, picked without a dynamic register index)
         float qe = 0.f, ke = 0.f;
@@ -192,10 +202,18 @@ __global__ __launch_bounds__(kBwdThreads) void backward_apply_kernel(const T* __
         }
         dq[i] = qe > 0.f ? a : 0.f;
         dk[i] = ke > 0.f ? bk : 0.f;
-        float c = 0.f;
+    }
+    // dV: this lane's four columns of rk dS[:, :d], a 16-byte read per row
+    {
+        f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e2 = 0; e2 < 16; ++e2) c = fmaf(fmaxf(k[e2], 0.f), dS[e2 * 17 + p * 4 + i], c);
-        dv[i] = c;
+        for (int e2 = 0; e2 < 16; ++e2) {
+            const f32x4 d4 = *(const f32x4*)(dS + e2 * kRowS + p * 4);
+            const float rk = fmaxf(k[e2], 0.f);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c[i] = fmaf(rk, d4[i], c[i]);
+        }
+        dv = c;
     }
     if (live) {
         T* out = d_qkv + tok * ts + h * 48 + p * 4;
