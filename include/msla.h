@@ -52,10 +52,10 @@
  *
  * Supported: head_dim == 16; scales[a] in {3, 5, 7}; n_scales <= 7;
  * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  msla_forward (and the
- * workspace query) also take head_dim 8 and 32 (MSLA_NHWC only, no options).  Heads of
- * 8 run in pairs on the head_dim-16 kernels (the call first writes the weights in that
- * arrangement into the workspace); heads of 32 have an aggregation kernel of their own
- * for fp16 / bf16 and plain vector-ALU kernels for the rest.  Anything else that is
+ * workspace query) also take head_dim 8 and 32 (no options).  Heads of 8 run in pairs
+ * on the head_dim-16 kernels (the call first writes the weights in that arrangement into
+ * the workspace); heads of 32 (MSLA_NHWC only) have an aggregation kernel of their own for
+ * fp16 / bf16 and plain vector-ALU kernels for the rest.  Anything else that is
  * otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
  */
 #ifndef MSLA_H_

@@ -352,11 +352,12 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
     if (layout != MSLA_NHWC && layout != MSLA_NCHW) return MSLA_ERR_INVALID_ARG;
     if (generic_head_dim(head_dim)) {
-        // head sizes 8 and 32: the plain kernels; token-major only, no options, no stage events, no residual
+        // head sizes 8 and 32: no options, no stage events, no residual; head size 32 token-major only
         if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
             !aligned16(w_dw) || !aligned16(w_gpw))
             return MSLA_ERR_INVALID_ARG;
-        if (layout != MSLA_NHWC || options != 0 || events != nullptr || residual != nullptr) return MSLA_ERR_UNSUPPORTED;
+        if (options != 0 || events != nullptr || residual != nullptr) return MSLA_ERR_UNSUPPORTED;
+        if (layout != MSLA_NHWC && !paired8(heads, head_dim)) return MSLA_ERR_UNSUPPORTED;
         if (paired8(heads, head_dim)) {
             // two heads of 8 as one head of 16: rearranged weights, then the head-size-16 module
             GenericPlan gp;     // (argument checks shared with the plain path)
