@@ -1,5 +1,6 @@
 // The FFN+DWConv half of the EfficientViT building block (Section 3.1: a depthwise convolution is
-// inserted into the FFN layer that follows the attention module; Fig. 2 left).  Declared reading (the paper prints no more than the sentence above):
+// inserted into the FFN layer that follows the attention module; Fig. 2 left).  Declared reading (the
+// paper prints no more than the sentence above):
 //   h   = act(W1 y)                      1x1 expand, C -> E
 //   g   = act(DW3x3(h))                  depthwise 3x3, stride 1, zero padding 1, cross-correlation
 //   out = y + W2 g                       1x1 project, E -> C, no activation, residual
@@ -194,15 +195,15 @@ __global__ __launch_bounds__(512) void ffn_dw_project_kernel(const T* __restrict
 
 // The same operation for the 16-bit storage types with the waves specialised: the depthwise pass is
 // vector-ALU work (144 mixed-precision FMAs a thread and slab), the projection matrix-core work, the
-// staging LDS traffic -- three different units, which a wave that does all three in turn leaves idle two
-// thirds of the time.  Sixteen waves: waves 0-7 (two per SIMD) only stage W2 slabs and issue matrix
-// instructions, waves 8-15 (two per SIMD) only stage halo tiles and do the depthwise pass.  Everything in LDS is double-buffered and one barrier ends each step.  In step i
+// staging LDS traffic -- three different units that a wave doing all three in turn keeps busy one at a
+// time.  Sixteen waves: waves 0-7 (two per SIMD) only stage W2 slabs and issue matrix instructions, waves
+// 8-15 (two per SIMD) only stage halo tiles and do the depthwise pass.  Everything in LDS is
+// double-buffered and one barrier ends each step.  In step i
 //   consumers   park W2 slab i+1, request slab i+2, multiply slab i  (token tile i%2 x weight tile i%2)
 //   producers   park halo i+2, request halo i+3, depthwise pass of slab i+1 -> token tile (i+1)%2
 // so every buffer written in a step was last read in the step before.  Rows are 128 bytes, unpadded, with
 // the 16-byte chunk index XOR-ed with (row / 2) % 8 (full rate for operand reads and row-order writes).
-// Requires one image's expanded map to
-// stay below 2^31 bytes (32-bit offsets in a buffer resource).
+// Requires one image's expanded map to stay below 2^31 bytes (32-bit offsets in a buffer resource).
 template <class T, int ACT>
 __global__ __launch_bounds__(1024) void ffn_dw_project_split_kernel(const T* __restrict__ h, const T* __restrict__ w_dw,
                                                                    const T* __restrict__ w2, const T* __restrict__ res,
