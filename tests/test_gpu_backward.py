@@ -35,7 +35,7 @@ def make(seed, dtype, B, N, heads, d=16):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("B,N,heads", [(1, 1, 1), (2, 37, 3), (1, 64, 2), (2, 1000, 4), (1, 4099, 2), (1, 300, 6), (8, 2048, 16)])
+@pytest.mark.parametrize("B,N,heads", [(1, 1, 1), (2, 37, 3), (1, 64, 2), (2, 1000, 4), (1, 4099, 2), (1, 300, 6), (8, 2048, 16), (8, 8192, 16)])
 def test_linear_attention_backward(dtype, B, N, heads):
     d, eps = 16, 1e-15
     print(f"linear attention backward {dtype} B={B} N={N} heads={heads}", flush=True)
