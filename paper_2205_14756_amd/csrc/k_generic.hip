@@ -1,17 +1,18 @@
 // The module for head sizes other than 16 (Section 3.1 fixes only "d channels per group"; 8 and 32 are
 // the other sizes the architecture family uses).
 //
-// Head size 32: multi-scale aggregation, the Eq. (3) state and the normalise-and-apply pass as plain
-// vector-ALU kernels templated on the head size D.  They follow the definitions step by step, fp32 sums
-// throughout, the same storage points as the head-size-16 path (projected Q/K/V and the Q tokens of every
-// branch are stored in the storage type; aggregated K and V only feed the state), and are not tuned: the
-// matrix-core kernels are built around 16 x 16 tiles.
+// Head size 32.  fp32 storage: multi-scale aggregation and the Eq. (3) state as plain vector-ALU kernels
+// templated on the head size D, following the definitions step by step with fp32 sums throughout (16-bit
+// storage takes the tiled matrix-core kernel of k_aggregate32.hip instead); all types: the fixed-order sum of
+// the partial states and the normalise-and-apply pass below.  The same storage points as the head-size-16
+// path: projected Q/K/V and the Q tokens of every branch are stored in the storage type; aggregated K and V
+// only feed the state.
 //
 //   generic_branch_state_kernel   one branch (raw, or depthwise k x k + grouped 1x1) of one (image, head,
 //                                 chunk of 64-token groups): writes that branch's Q tokens, accumulates
 //                                 KV = sum_n relu(K_n)^T [V_n, 1] into a per-workgroup partial state
 //   generic_state_finalize_kernel fixed-order sum of the partial states
-//   generic_apply_kernel          att_n = relu(Q_n) KV[:, :D] / (relu(Q_n) KV[:, D] + eps)
+//   generic_apply_kernel          att_n = relu(Q_n) KV[:, :D] / (relu(Q_n) KV[:, D] + eps), on the matrix cores in fp32
 //
 // Head size 8 needs no kernels of its own: two heads side by side are one head of 16 whose grouped 1x1 is
 // block-diagonal and whose state is used block by block (pair_head8_weights_kernel arranges the weights
@@ -140,70 +141,114 @@ __global__ __launch_bounds__(kGenThreads) void generic_state_finalize_kernel(con
     }
 }
 
-// one workgroup = 256 tokens of one (image, head-branch m): a thread per token.  The state sits in LDS with
-// its rows padded to a multiple of four floats, so that a row is read four values at a time (every lane reads
-// the same address: a broadcast); a token's Q row comes in and its attention row goes out as 16-byte vectors.
+// Normalise-and-apply for heads of 32 channels on the matrix cores in fp32 (the operands -- rectified Q
+// converted from the storage type, the fp32 state -- go in exactly).  A workgroup owns four neighbouring
+// head-branches, one per wave (256 contiguous bytes of a token's row in the 16-bit types: whole lines), and
+// kApplyGroups groups of 16 tokens; lane (token x16, q) holds channels 8q..8q+7 of its token (one 16-byte
+// load in, one 16-byte store out in the 16-bit types).  The 32 x 32 product is a 2 x 2 arrangement of
+// 16 x 16 x 16 contractions whose slots are numbered to fit that: contraction slot (q, r) of chunk jc is
+// channel e = 8q + 4jc + r, output row 4q + r of chunk jo is channel f = 8q + 4jo + r.
+constexpr int kApplyGroups = 8;
+
+template <class T>
+struct Row8 {                       // a lane's eight channels as loaded
+    u32x4 v[sizeof(T) == 4 ? 2 : 1];
+};
+template <class T>
+__device__ __forceinline__ Row8<T> load_row8(const T* p) {
+    Row8<T> r;
+    r.v[0] = *(const u32x4*)p;
+    if constexpr (sizeof(T) == 4) r.v[1] = *(const u32x4*)(p + 4);
+    return r;
+}
+template <class T>
+__device__ __forceinline__ void widen_row8(const Row8<T>& r, float* out) {
+    if constexpr (sizeof(T) == 4) {
+        const f32x4 a = __builtin_bit_cast(f32x4, r.v[0]), b = __builtin_bit_cast(f32x4, r.v[1]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = a[i], out[4 + i] = b[i];
+    } else {
+        const typename Traits<T>::Vec x = __builtin_bit_cast(typename Traits<T>::Vec, r.v[0]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = Traits<T>::to_f32(x[i]);
+    }
+}
+template <class T>
+__device__ __forceinline__ void store_row8(T* p, const float* v) {
+    if constexpr (sizeof(T) == 4) {
+        *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
+        *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+    } else {
+        typename Traits<T>::Vec x;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = Traits<T>::from_f32(v[i]);
+        *(u32x4*)p = __builtin_bit_cast(u32x4, x);
+    }
+}
+
 template <class T, int D>
 __global__ __launch_bounds__(kGenThreads) void generic_apply_kernel(const T* __restrict__ q_ms, const float* __restrict__ kv32,
                                                                     T* __restrict__ att, int N, int n_hb, int blocks_per_image,
                                                                     float eps) {
+    static_assert(D == 32, "2 x 2 blocks of 16");
     constexpr int kState = D * (D + 1);
-    constexpr int kRow = D + 4;                     // padded row: KV[e][0..D-1], Ksum[e], 3 unused
-    constexpr int kVecElems = 16 / (int)sizeof(T);  // elements per 16-byte vector
-    static_assert(D % 8 == 0, "whole vectors");
-    __shared__ __attribute__((aligned(16))) float St[D * kRow];
-    const int m = blockIdx.x % n_hb;
-    const int nb = (blockIdx.x / n_hb) % blocks_per_image;
-    const int b = blockIdx.x / (n_hb * blocks_per_image);
-    for (int j = threadIdx.x; j < kState; j += kGenThreads) {
-        const int e = j / (D + 1), f = j - e * (D + 1);
-        St[e * kRow + f] = kv32[((long)b * n_hb + m) * kState + j];
-    }
-    __syncthreads();
-    const int n = nb * kGenThreads + threadIdx.x;
-    if (n >= N) return;
-    const long row = ((long)b * N + n) * ((long)n_hb * D) + (long)m * D;
-    float rq[D];
+    typedef Traits<float> F32;
+    const int quads = (n_hb + 3) / 4;
+    const int lane = lane_id(), wave = threadIdx.x >> 6, x16 = lane & 15, q = lane >> 4;
+    const int m = (blockIdx.x % quads) * 4 + wave;
+    const int nb = (blockIdx.x / quads) % blocks_per_image;
+    const int b = blockIdx.x / (quads * blocks_per_image);
+    if (m >= n_hb) return;      // no barrier below
+    const float* st = kv32 + ((long)b * n_hb + m) * kState;
+    // state operands: S[jc][jo] lane (x16, q) = KV[8q + 4jc + r][8(x16 >> 2) + 4jo + (x16 & 3)], r = 0..3
+    f32x4 S[2][2];
+    float ksum[8];
+    const int fo = 8 * (x16 >> 2) + (x16 & 3);
 #pragma unroll
-    for (int v = 0; v < D / kVecElems; ++v) {
-        const u32x4 raw = *(const u32x4*)(q_ms + row + v * kVecElems);
-        if constexpr (sizeof(T) == 4) {
-            const f32x4 x = __builtin_bit_cast(f32x4, raw);
+    for (int jc = 0; jc < 2; ++jc)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) rq[v * 4 + i] = fmaxf(x[i], 0.f);
-        } else {
-            const typename Traits<T>::Vec x = __builtin_bit_cast(typename Traits<T>::Vec, raw);
+        for (int jo = 0; jo < 2; ++jo)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rq[v * 8 + i] = fmaxf(Traits<T>::to_f32(x[i]), 0.f);
+            for (int r = 0; r < 4; ++r) S[jc][jo][r] = st[(8 * q + 4 * jc + r) * (D + 1) + fo + 4 * jo];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ksum[i] = st[(8 * q + i) * (D + 1) + D];
+
+    const long pitch = (long)n_hb * D;
+    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+    auto fetch = [&](int u, bool& live, long& at) {
+        const long n = ((long)nb * kApplyGroups + u) * 16 + x16;
+        live = n < N;
+        at = ((long)b * N + (live ? n : 0)) * pitch + (long)m * D + 8 * q;     // a token past the end reads token 0
+        return load_row8<T>(q_ms + at);
+    };
+    bool live, live_next = false;
+    long at, at_next = 0;
+    Row8<T> cur = fetch(0, live, at), next = cur;
+#pragma unroll
+    for (int u = 0; u < kApplyGroups; ++u) {
+        if (u + 1 < kApplyGroups) next = fetch(u + 1, live_next, at_next);
+        float rq[8];
+        widen_row8<T>(cur, rq);
+        float den = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            rq[i] = live ? fmaxf(rq[i], 0.f) : 0.f;
+            den = fmaf(rq[i], ksum[i], den);
         }
-    }
-    float num[D];
-#pragma unroll
-    for (int f = 0; f < D; ++f) num[f] = 0.f;
-    float den = eps;
-#pragma unroll
-    for (int e = 0; e < D; ++e) {
-        den = fmaf(rq[e], St[e * kRow + D], den);
-#pragma unroll
-        for (int f4 = 0; f4 < D; f4 += 4) {
-            const f32x4 s4 = *(const f32x4*)(St + e * kRow + f4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) num[f4 + i] = fmaf(rq[e], s4[i], num[f4 + i]);
+        den += __shfl_xor(den, 16);
+        den += __shfl_xor(den, 32);
+        const f32x4 lo = {rq[0], rq[1], rq[2], rq[3]}, hi = {rq[4], rq[5], rq[6], rq[7]};
+        const f32x4 n0 = F32::mma16(F32::mma16(z, S[0][0], lo), S[1][0], hi);
+        const f32x4 n1 = F32::mma16(F32::mma16(z, S[0][1], lo), S[1][1], hi);
+        const float inv = 1.0f / (den + eps);
+        if (live) {
+            const float o[8] = {n0[0] * inv, n0[1] * inv, n0[2] * inv, n0[3] * inv,
+                                n1[0] * inv, n1[1] * inv, n1[2] * inv, n1[3] * inv};
+            store_row8<T>(att + at, o);
         }
-    }
-    const float inv = 1.0f / den;
-#pragma unroll
-    for (int v = 0; v < D / kVecElems; ++v) {
-        u32x4 raw;
-        if constexpr (sizeof(T) == 4) {
-            raw = __builtin_bit_cast(u32x4, f32x4{num[v * 4] * inv, num[v * 4 + 1] * inv, num[v * 4 + 2] * inv, num[v * 4 + 3] * inv});
-        } else {
-            typename Traits<T>::Vec x;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = Traits<T>::from_f32(num[v * 8 + i] * inv);
-            raw = __builtin_bit_cast(u32x4, x);
-        }
-        *(u32x4*)(att + row + v * kVecElems) = raw;
+        cur = next;
+        live = live_next;
+        at = at_next;
     }
 }
 
@@ -216,8 +261,8 @@ hipError_t finish_generic(const GenericArgs& a, int N, hipStream_t stream) {
                        a.kv32, a.nchunks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int bpi = (N + kGenThreads - 1) / kGenThreads;
-    const long nb2 = (long)a.B * S * a.heads * bpi;
+    const int bpi = (N + 16 * kApplyGroups - 1) / (16 * kApplyGroups);
+    const long nb2 = (long)a.B * ((S * a.heads + 3) / 4) * bpi;
     if (nb2 > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((generic_apply_kernel<T, D>), dim3((unsigned)nb2), dim3(kGenThreads), 0, stream, (const T*)a.q_ms, a.kv32,
                        (T*)a.att, N, S * a.heads, bpi, a.eps);
