@@ -4,7 +4,8 @@
 //
 // The form of the general head-size-16 kernel (k_aggregate.hip) with every 16 x 16 block doubled: one
 // workgroup owns one (image, head) and a run of 8 x 32-token tiles; per tile it stages the halo tile of the
-// head's 96 raw channels in LDS, and each of its 4 waves takes 2 tile rows.  A lane (strip, q) owns 4
+// head's raw K, V and Q channels in LDS, one map at a time (the next one on its way while the current one is
+// swept), and each of its 4 waves takes 2 tile rows.  A lane (strip, q) owns 4
 // consecutive tokens and channels 4q..4q+3 of one 16-channel block of Q, K or V and slides the k x k window
 // along its strip in registers (fp32 sums), block after block.  The grouped 1x1 is a 2 x 2 arrangement of
 // 16x16x16 matrix instructions, relu(K)^T V a 2 x 2 arrangement of accumulators contracted over the tokens;
@@ -28,10 +29,12 @@ template <class T, int KS>
 struct Agg32Lds {
     static constexpr int P = (KS - 1) / 2;
     static constexpr int LH = TH + 2 * P, LW = TW + 2 * P;
-    // 96 channels + 8 bytes: a strip (4 pixels) is then 200 words on, 8 banks mod 32, which spreads the 64
-    // lanes' 8-byte reads evenly over the banks
-    static constexpr int kPixBytes = 3 * D32 * (int)sizeof(T) + 8;
-    static constexpr int kTileBytes = LH * LW * kPixBytes;
+    // One map (Q, K or V: 32 channels) of the halo tile at a time, two buffers: the next map is fetched while
+    // the current one is swept, and two workgroups fit a CU.  32 channels + 8 bytes a pixel: a strip (4
+    // pixels) is then 72 words on, 8 banks mod 32 (see lane_at in the kernel for the banks' low bits).
+    static constexpr int kPixBytes = D32 * (int)sizeof(T) + 8;
+    static constexpr int kMapBytes = LH * LW * kPixBytes;
+    static constexpr int kTileBytes = 2 * kMapBytes;
     static constexpr int kWtsBytes = 3 * KS * KS * D32 * 4;          // fp32 [t][tap][32 ch]
     // per wave: [branch][K block][V block][lane] accumulator quads, then [branch][32] Ksum
     static constexpr int kWaveFloats = 2 * NB * NB * 256 + 2 * D32;
@@ -106,30 +109,61 @@ __global__ __launch_bounds__(kThreads32) void aggregate32_kernel(AggregateArgs a
     // this lane's strip inside the tile
     const int srow = wave * 2 + (x16 >> 3);
     const int scol = (x16 & 7) * 4;
+    // Byte offset of pixel scol + c inside a tile row, this lane's channel quad included.  The two 16-byte
+    // halves of every 32 bytes of a pixel are swapped in pixels whose column has bit 4 set: the 32 lanes
+    // that an 8-byte read serves together (q = 0, 1) would otherwise use half of the banks twice (a
+    // strip's 800 bytes and a tile row are both 8 banks on, which leaves the banks' low bits to q).
+    // (scol is a multiple of 4, so the bit is the same for the four pixels scol + 4j .. scol + 4j + 3: one
+    // base per j, the pixels of a block at constant distances from it)
+    int lane_at[(4 + KS - 1 + 3) / 4];
+#pragma unroll
+    for (int j = 0; j < (4 + KS - 1 + 3) / 4; ++j)
+        lane_at[j] = scol * L::kPixBytes + ((q * 4 * SZ) ^ ((((scol + 4 * j) >> 4) & 1) * 16));
+
+    // Stages: (tile, pass) with the passes in the order K, V, Q.  A stage's map goes global -> registers while
+    // the stage before it is swept, registers -> LDS after that sweep, one barrier a stage.
+    constexpr int VPT = D32 * SZ / 16;
+    constexpr int kItems = L::LH * L::LW * VPT;                    // 16-byte vectors of one map's halo tile
+    constexpr int kPer = (kItems + kThreads32 - 1) / kThreads32;
+    u32x4 pre[kPer];
+    auto map_of = [](int pass) { return pass == 0 ? 1 : pass == 1 ? 2 : 0; };
+    auto fetch = [&](int tile_id, int pass) {
+        const int ty0 = (tile_id / tiles_x) * TH, tx0 = (tile_id % tiles_x) * TW;
+        const int t = map_of(pass);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int it = threadIdx.x + j * kThreads32;
+            const int vi = it % VPT, pix = it / VPT;
+            const int ly = pix / L::LW, lx = pix - ly * L::LW;
+            const int gy = ty0 - P + ly, gx = tx0 - P + lx;
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (it < kItems && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W)
+                val = *(const u32x4*)(maps[t] + (img_tok0 + (long)gy * a.W + gx) * map_ts[t] + vi * Tr::kVec);
+            pre[j] = val;
+        }
+    };
+    auto stash = [&](char* buf) {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int it = threadIdx.x + j * kThreads32;
+            if (it < kItems) {
+                const int vi = it % VPT, pix = it / VPT;
+                const int lx = pix % L::LW;
+                char* dst = buf + pix * L::kPixBytes + ((vi * 16) ^ (((lx >> 4) & 1) * 16));
+                ((u32x2*)dst)[0] = u32x2{pre[j][0], pre[j][1]};
+                ((u32x2*)dst)[1] = u32x2{pre[j][2], pre[j][3]};
+            }
+        }
+    };
+    int cur = 0;
+    if (tile_begin < tile_end) {
+        fetch(tile_begin, 0);
+        stash(tile);
+    }
+    __syncthreads();   // first map staged, wts written
 
     for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
         const int ty0 = (tile_id / tiles_x) * TH, tx0 = (tile_id % tiles_x) * TW;
-        __syncthreads();   // previous tile fully consumed (and wts written, first time)
-        // halo tile: one 16-byte vector per item (pixel, map, vector)
-        {
-            constexpr int VPT = D32 * SZ / 16;
-            constexpr int kItems = L::LH * L::LW * 3 * VPT;
-            for (int it = threadIdx.x; it < kItems; it += kThreads32) {
-                const int vi = it % VPT;
-                const int t = (it / VPT) % 3;
-                const int pix = it / (3 * VPT);
-                const int ly = pix / L::LW, lx = pix - ly * L::LW;
-                const int gy = ty0 - P + ly, gx = tx0 - P + lx;
-                u32x4 val = {0u, 0u, 0u, 0u};
-                if (gy >= 0 && gy < a.H && gx >= 0 && gx < a.W)
-                    val = *(const u32x4*)(maps[t] + (img_tok0 + (long)gy * a.W + gx) * map_ts[t] + vi * Tr::kVec);
-                char* dst = tile + pix * L::kPixBytes + t * D32 * SZ + vi * 16;
-                ((u32x2*)dst)[0] = u32x2{val[0], val[1]};
-                ((u32x2*)dst)[1] = u32x2{val[2], val[3]};
-            }
-        }
-        __syncthreads();
-
         const int gy = ty0 + srow, gx0 = tx0 + scol;
         bool valid[4];
 #pragma unroll
@@ -144,6 +178,9 @@ __global__ __launch_bounds__(kThreads32) void aggregate32_kernel(AggregateArgs a
             // Q's sums always as hi + lo: the sign of an aggregated Q component decides what passes the
             // rectifier of Eq. (2), so it keeps its fp32 accuracy up to its store
             const bool wide = Tr::kHiLo || t == 0;
+            const bool more = pass < 2 || tile_id + 1 < tile_end;
+            if (more) fetch(pass < 2 ? tile_id : tile_id + 1, pass < 2 ? pass + 1 : 0);
+            const char* map = tile + cur * L::kMapBytes;
             Frag dwf[NB][4], dwl[NB][4], center[NB][4];
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) {
@@ -152,18 +189,18 @@ __global__ __launch_bounds__(kThreads32) void aggregate32_kernel(AggregateArgs a
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
-                const char* src = tile + (t * D32 + ib * 16 + q * 4) * SZ;
+                const char* src = map + ib * 16 * SZ;
                 const float* wt = wts + t * KS * KS * D32 + ib * 16 + q * 4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    center[ib][r] = load_frag<T>(src + ((srow + P) * L::LW + scol + r + P) * L::kPixBytes);
+                    center[ib][r] = load_frag<T>(src + (srow + P) * L::LW * L::kPixBytes + lane_at[(r + P) >> 2] + (r + P) * L::kPixBytes);
                 // one filter row per iteration: 4+KS-1 pixels feed 4 tokens x KS taps x 4 channels
 #pragma unroll 1
                 for (int u = 0; u < KS; ++u) {
                     Frag rowv[4 + KS - 1];
 #pragma unroll
                     for (int c = 0; c < 4 + KS - 1; ++c)
-                        rowv[c] = load_frag<T>(src + ((srow + u) * L::LW + scol + c) * L::kPixBytes);
+                        rowv[c] = load_frag<T>(src + (srow + u) * L::LW * L::kPixBytes + lane_at[c >> 2] + c * L::kPixBytes);
 #pragma unroll
                     for (int v = 0; v < KS; ++v) {
                         const f32x4 w4 = *(const f32x4*)(wt + (u * KS + v) * D32);
@@ -251,6 +288,10 @@ __global__ __launch_bounds__(kThreads32) void aggregate32_kernel(AggregateArgs a
                     }
                 }
             }
+            // the next stage's map: registers -> the other buffer (free since the barrier of the stage before)
+            if (more) stash(tile + (cur ^ 1) * L::kMapBytes);
+            __syncthreads();
+            cur ^= 1;
         }
     }
 
