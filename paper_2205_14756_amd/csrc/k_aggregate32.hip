@@ -42,8 +42,13 @@ struct Agg32Lds {
     static constexpr int kBytes = (kTileBytes > kRedBytes ? kTileBytes : kRedBytes) + kWtsBytes;
 };
 
+// (build knob, for experiments: waves a SIMD the register allocation is held to; 1 = no cap)
+#ifndef MSLA_AGG32_WAVES
+#define MSLA_AGG32_WAVES 1
+#endif
+
 template <class T, int KS>
-__global__ __launch_bounds__(kThreads32) void aggregate32_kernel(AggregateArgs a) {
+__global__ __launch_bounds__(kThreads32, MSLA_AGG32_WAVES) void aggregate32_kernel(AggregateArgs a) {
     static_assert(sizeof(T) == 2, "16-bit storage types");
     typedef Traits<T> Tr;
     typedef typename Tr::Frag Frag;
