@@ -6,8 +6,10 @@
 // per image / branch / head, only  KV = sum_n relu(K_n)^T [V_n, 1].
 //
 // One workgroup owns one (image, head) and a run of 8 x 32-token tiles.  Per
-// tile it stages the halo tile of the head's 48 raw channels in LDS, and each
-// of its 4 waves takes 2 tile rows (64 tokens):
+// tile it stages the halo tile of the head's raw K, V and Q channels in LDS, one
+// map at a time (the next one is fetched into registers while the current one is
+// swept, and written to the other of two buffers after it), and each of its 4
+// waves takes 2 tile rows (64 tokens):
 //   - a lane (i, q) owns a strip of 4 consecutive tokens and channels 4q..4q+3
 //     of one of Q/K/V; it slides the k x k window along the strip in registers
 //     (fp32 sums), so the depthwise result is already an MFMA operand;
@@ -35,10 +37,12 @@ template <class T, int KS>
 struct AggLds {
     static constexpr int P = (KS - 1) / 2;
     static constexpr int LH = TH + 2 * P, LW = TW + 2 * P;
-    // 48 channels + 8 bytes: the strip stride (4 pixels) is then 8 banks mod 32,
-    // which spreads the 64 lanes' 8-byte reads evenly over the banks.
-    static constexpr int kPixBytes = 48 * (int)sizeof(T) + 8;
-    static constexpr int kTileBytes = LH * LW * kPixBytes;
+    // One map (Q, K or V: 16 channels) of the halo tile at a time, two buffers: the next map is fetched while
+    // the current one is swept.  16 channels + 8 bytes a pixel: the strip stride (4 pixels) is then 8 banks
+    // mod 32, which spreads the 64 lanes' 8-byte reads over the banks.
+    static constexpr int kPixBytes = 16 * (int)sizeof(T) + 8;
+    static constexpr int kMapBytes = LH * LW * kPixBytes;
+    static constexpr int kTileBytes = 2 * kMapBytes;
     static constexpr int kWtsBytes = 3 * KS * KS * 16 * 4;     // fp32 [t][tap][16 ch]
     static constexpr int kRedBytes = 4 * (2 * 256 + 2 * 16) * 4;   // per wave: 2 x 64 lanes x 4 + 2 x 16 Ksum
     static constexpr int kBytes = (kTileBytes > kRedBytes ? kTileBytes : kRedBytes) + kWtsBytes;
@@ -50,35 +54,6 @@ struct HeadMaps {
     const T *q, *k, *v;
     long q_ts, k_ts, v_ts;   // elements per token
 };
-
-// Halo tile of one of the three maps: one 16-byte vector per loop item (pixel, vector).
-template <class T, int KS>
-__device__ __forceinline__ void load_halo_map(char* tile, const T* __restrict__ base, long ts, int t,
-                                              long img_tok0, int H, int W, int ty0, int tx0) {
-    typedef AggLds<T, KS> L;
-    constexpr int VPT = 16 * (int)sizeof(T) / 16;   // vectors per (pixel, map)
-    constexpr int kItems = L::LH * L::LW * VPT;
-    for (int it = threadIdx.x; it < kItems; it += kAggThreads) {
-        const int vi = it % VPT;
-        const int pix = it / VPT;
-        const int ly = pix / L::LW, lx = pix - ly * L::LW;
-        const int gy = ty0 - L::P + ly, gx = tx0 - L::P + lx;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (gy >= 0 && gy < H && gx >= 0 && gx < W)
-            val = *(const u32x4*)(base + (img_tok0 + (long)gy * W + gx) * ts + vi * Traits<T>::kVec);
-        char* dst = tile + pix * L::kPixBytes + t * 16 * (int)sizeof(T) + vi * 16;
-        ((u32x2*)dst)[0] = u32x2{val[0], val[1]};
-        ((u32x2*)dst)[1] = u32x2{val[2], val[3]};
-    }
-}
-
-template <class T, int KS>
-__device__ __forceinline__ void load_halo_tile(char* tile, const HeadMaps<T>& maps, long img_tok0,
-                                               int H, int W, int ty0, int tx0) {
-    load_halo_map<T, KS>(tile, maps.q, maps.q_ts, 0, img_tok0, H, W, ty0, tx0);
-    load_halo_map<T, KS>(tile, maps.k, maps.k_ts, 1, img_tok0, H, W, ty0, tx0);
-    load_halo_map<T, KS>(tile, maps.v, maps.v_ts, 2, img_tok0, H, W, ty0, tx0);
-}
 
 template <class T, int KS>
 __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a) {
@@ -136,12 +111,50 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a)
     const int srow = wave * 2 + (x16 >> 3);
     const int scol = (x16 & 7) * 4;
 
+    // Stages: (tile, pass) with the passes in the order K, V, Q.  A stage's map goes global -> registers while
+    // the stage before it is swept, registers -> LDS after that sweep, one barrier a stage.
+    constexpr int SZ = (int)sizeof(T);
+    constexpr int VPT = 16 * SZ / 16;                              // 16-byte vectors per pixel of one map
+    constexpr int kItems = L::LH * L::LW * VPT;
+    constexpr int kPer = (kItems + kAggThreads - 1) / kAggThreads;
+    u32x4 pre[kPer];
+    auto fetch = [&](int tile_id, int pass) {
+        const int ty0 = (tile_id / tiles_x) * TH, tx0 = (tile_id % tiles_x) * TW;
+        const T* base = pass == 0 ? maps.k : pass == 1 ? maps.v : maps.q;
+        const long ts = pass == 0 ? maps.k_ts : pass == 1 ? maps.v_ts : maps.q_ts;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int it = threadIdx.x + j * kAggThreads;
+            const int vi = it % VPT, pix = it / VPT;
+            const int ly = pix / L::LW, lx = pix - ly * L::LW;
+            const int gy = ty0 - P + ly, gx = tx0 - P + lx;
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (it < kItems && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W)
+                val = *(const u32x4*)(base + (img_tok0 + (long)gy * a.W + gx) * ts + vi * Tr::kVec);
+            pre[j] = val;
+        }
+    };
+    auto stash = [&](char* buf) {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int it = threadIdx.x + j * kAggThreads;
+            if (it < kItems) {
+                const int vi = it % VPT, pix = it / VPT;
+                char* dst = buf + pix * L::kPixBytes + vi * 16;
+                ((u32x2*)dst)[0] = u32x2{pre[j][0], pre[j][1]};
+                ((u32x2*)dst)[1] = u32x2{pre[j][2], pre[j][3]};
+            }
+        }
+    };
+    int cur = 0;
+    if (tile_begin < tile_end) {
+        fetch(tile_begin, 0);
+        stash(tile);
+    }
+    __syncthreads();   // first map staged, wts written
+
     for (int tile_id = tile_begin; tile_id < tile_end; ++tile_id) {
         const int ty0 = (tile_id / tiles_x) * TH, tx0 = (tile_id % tiles_x) * TW;
-        __syncthreads();   // previous tile fully consumed (and wts written, first time)
-        load_halo_tile<T, KS>(tile, maps, img_tok0, a.H, a.W, ty0, tx0);
-        __syncthreads();
-
         const int gy = ty0 + srow, gx0 = tx0 + scol;
         bool valid[4];
 #pragma unroll
@@ -158,7 +171,9 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a)
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
-            const char* src = tile + t * 16 * (int)sizeof(T) + q * 4 * (int)sizeof(T);
+            const bool more = pass < 2 || tile_id + 1 < tile_end;
+            if (more) fetch(pass < 2 ? tile_id : tile_id + 1, pass < 2 ? pass + 1 : 0);
+            const char* src = tile + cur * L::kMapBytes + q * 4 * SZ;
             const float* wt = wts + t * KS * KS * 16 + q * 4;
             // raw tokens of the strip (the centre tap), for the raw branch / the raw-Q copy
             Frag center[4];
@@ -239,6 +254,10 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(AggregateArgs a)
                     }
                 }
             }
+            // the next stage's map: registers -> the other buffer (free since the barrier of the stage before)
+            if (more) stash(tile + (cur ^ 1) * L::kMapBytes);
+            __syncthreads();
+            cur ^= 1;
         }
     }
 
