@@ -199,24 +199,40 @@ __global__ __launch_bounds__(kThreads32, MSLA_AGG32_WAVES) void aggregate32_kern
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     center[ib][r] = load_frag<T>(src + (srow + P) * L::LW * L::kPixBytes + lane_at[(r + P) >> 2] + (r + P) * L::kPixBytes);
-                // one filter row per iteration: 4+KS-1 pixels feed 4 tokens x KS taps x 4 channels
-#pragma unroll 1
-                for (int u = 0; u < KS; ++u) {
-                    Frag rowv[4 + KS - 1];
+                // one filter row at a time: 4+KS-1 pixels feed 4 tokens x KS taps x 4 channels.  A row's pixels
+                // and taps are read from LDS while the row before it is worked on (two register sets in turn:
+                // with one wave a SIMD nothing else hides those reads)
+                struct Row {
+                    Frag px[4 + KS - 1];
+                    f32x4 w[KS];
+                };
+                auto read_row = [&](int u, Row& row) {
 #pragma unroll
                     for (int c = 0; c < 4 + KS - 1; ++c)
-                        rowv[c] = load_frag<T>(src + (srow + u) * L::LW * L::kPixBytes + lane_at[c >> 2] + c * L::kPixBytes);
+                        row.px[c] = load_frag<T>(src + (srow + u) * L::LW * L::kPixBytes + lane_at[c >> 2] + c * L::kPixBytes);
 #pragma unroll
-                    for (int v = 0; v < KS; ++v) {
-                        const f32x4 w4 = *(const f32x4*)(wt + (u * KS + v) * D32);
+                    for (int v = 0; v < KS; ++v) row.w[v] = *(const f32x4*)(wt + (u * KS + v) * D32);
+                };
+                auto sweep_row = [&](const Row& row) {
+#pragma unroll
+                    for (int v = 0; v < KS; ++v)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const f32x4 d4 = frag_to_f32<T>(rowv[r + v]);
+                            const f32x4 d4 = frag_to_f32<T>(row.px[r + v]);
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(w4[c], d4[c], acc[r][c]);
+                            for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(row.w[v][c], d4[c], acc[r][c]);
                         }
-                    }
+                };
+                Row even, odd;
+                read_row(0, even);
+#pragma unroll 1
+                for (int u = 0; u + 1 < KS; u += 2) {      // KS is odd: u + 2 <= KS - 1 here
+                    read_row(u + 1, odd);
+                    sweep_row(even);
+                    read_row(u + 2, even);
+                    sweep_row(odd);
                 }
+                sweep_row(even);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     f32x4 a4 = {acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
