@@ -54,8 +54,8 @@
  * C and Ct multiples of 16; with MSLA_NCHW also C <= 2*Ct.  msla_forward (and the
  * workspace query) also take head_dim 8 and 32 (no options).  Heads of 8 run in pairs
  * on the head_dim-16 kernels (the call first writes the weights in that arrangement into
- * the workspace); heads of 32 (MSLA_NHWC only) have an aggregation kernel of their own for
- * fp16 / bf16 and plain vector-ALU kernels for the rest.  Anything else that is
+ * the workspace); heads of 32 (with MSLA_NCHW: C <= 3*Ct) have an aggregation kernel of their
+ * own for fp16 / bf16 and a plain vector-ALU one for fp32.  Anything else that is
  * otherwise well-formed returns MSLA_ERR_UNSUPPORTED.
  */
 #ifndef MSLA_H_

@@ -274,12 +274,22 @@ msla_status paired8_plan(int B, int C, int H, int W, int heads, const int* scale
 
 msla_status generic_forward(const void* x, const void* w_qkv, const void* w_dw, const void* w_gpw, const void* w_proj,
                             void* out, void* workspace, size_t workspace_bytes, int B, int C, int H, int W, int heads,
-                            int head_dim, const int* scales, int n_scales, float eps, msla_dtype dt, hipStream_t hs) {
+                            int head_dim, const int* scales, int n_scales, float eps, msla_dtype dt, msla_layout layout,
+                            hipStream_t hs) {
     GenericPlan p;
     const msla_status st = generic_plan(B, C, H, W, heads, head_dim, scales, n_scales, (int)dt, &p);
     if (st != MSLA_OK) return st;
     if (workspace_bytes < p.total) return MSLA_ERR_WORKSPACE;
+    // channel-planar x / out: x is turned into token-major form in `out` (free until the last kernel), the
+    // token-major result is parked where the projected Q/K/V lived and turned back into `out`
+    if (layout == MSLA_NCHW && C > 3 * p.Ct) return MSLA_ERR_UNSUPPORTED;
     char* ws = static_cast<char*>(workspace);
+    void* out_tok = out;
+    if (layout == MSLA_NCHW) {
+        if (msla::launch_transpose((int)dt, x, out, B, C, H * W, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+        x = out;
+        out_tok = ws + p.qkv;
+    }
     if (msla::launch_linear((int)dt, x, w_qkv, ws + p.qkv, p.T, C, 3 * p.Ct, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
     msla::GenericArgs a;
     a.qkv = ws + p.qkv; a.w_dw = w_dw; a.w_gpw = w_gpw; a.q_ms = ws + p.q_ms;
@@ -289,7 +299,9 @@ msla_status generic_forward(const void* x, const void* w_qkv, const void* w_dw, 
     for (int i = 0; i < n_scales; ++i) a.scales[i] = scales[i];
     a.nchunks = p.nchunks; a.eps = eps;
     if (msla::launch_generic_core((int)dt, a, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
-    if (msla::launch_linear((int)dt, ws + p.att, w_proj, out, p.T, p.S * p.Ct, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (msla::launch_linear((int)dt, ws + p.att, w_proj, out_tok, p.T, p.S * p.Ct, C, hs) != hipSuccess) return MSLA_ERR_LAUNCH;
+    if (layout == MSLA_NCHW && msla::launch_transpose((int)dt, out_tok, out, B, H * W, C, hs) != hipSuccess)
+        return MSLA_ERR_LAUNCH;
     return MSLA_OK;
 }
 
@@ -352,12 +364,12 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
     if (!(eps >= 0.0f)) return MSLA_ERR_INVALID_ARG;
     if (layout != MSLA_NHWC && layout != MSLA_NCHW) return MSLA_ERR_INVALID_ARG;
     if (generic_head_dim(head_dim)) {
-        // head sizes 8 and 32: no options, no stage events, no residual; head size 32 token-major only
+        // head sizes 8 and 32: no options, no stage events, no residual
         if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
             !aligned16(w_dw) || !aligned16(w_gpw))
             return MSLA_ERR_INVALID_ARG;
         if (options != 0 || events != nullptr || residual != nullptr) return MSLA_ERR_UNSUPPORTED;
-        if (layout != MSLA_NHWC && !paired8(heads, head_dim)) return MSLA_ERR_UNSUPPORTED;
+        if (layout != MSLA_NHWC && !paired8(heads, head_dim) && head_dim != 32) return MSLA_ERR_UNSUPPORTED;
         if (paired8(heads, head_dim)) {
             // two heads of 8 as one head of 16: rearranged weights, then the head-size-16 module
             GenericPlan gp;     // (argument checks shared with the plain path)
@@ -376,7 +388,7 @@ static msla_status forward_impl(const void* x, const void* w_qkv, const void* w_
                                 heads / 2, 16, scales, n_scales, eps, dt, layout, stream, nullptr, 0u, nullptr, 8);
         }
         return generic_forward(x, w_qkv, w_dw, w_gpw, w_proj, out, workspace, workspace_bytes, B, C, H, W, heads, head_dim,
-                               scales, n_scales, eps, dt, static_cast<hipStream_t>(stream));
+                               scales, n_scales, eps, dt, layout, static_cast<hipStream_t>(stream));
     }
     if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(w_proj) || !aligned16(out) || !aligned16(workspace) ||
         !aligned16(w_dw) || !aligned16(w_gpw))

@@ -302,7 +302,7 @@ void run_module(const Mod& m, int dt) {
     g_case = std::string("msla_forward, one byte of workspace short ") + tag;
     expect(msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, out, ws, ws_bytes - 1, m.B, m.C, m.H, m.W, m.heads, m.d, sc, ns, 1e-15f,
                         mdt, MSLA_NHWC, nullptr), MSLA_ERR_WORKSPACE, "forward with a short workspace");
-    if (m.d != 32 && m.C <= 2 * Ct) {
+    if (m.C <= (m.d == 32 ? 3 : 2) * Ct) {
         g_case = std::string("msla_forward NCHW ") + tag;
         expect(msla_forward(x, w_qkv, w_dw, w_gpw, w_proj, out, ws, ws_bytes, m.B, m.C, m.H, m.W, m.heads, m.d, sc, ns, 1e-15f,
                             mdt, MSLA_NCHW, nullptr), MSLA_OK, "forward, channel-planar");

@@ -112,7 +112,8 @@ def test_forward_rejects_bad_arguments_before_launching(lib):
     assert _fwd(lib, H=0) == INVALID
     assert _fwd(lib, layout=1, C=256) == UNSUPPORTED  # channel-planar needs C <= 2 * heads * head_dim
     assert _fwd(lib, d=24, C=96) == UNSUPPORTED
-    assert _fwd(lib, d=32, heads=2, layout=1) == UNSUPPORTED     # head_dim 8 / 32: token-major only
+    assert _fwd(lib, d=32, heads=2, C=256, layout=1) == UNSUPPORTED   # ... with heads of 32: C <= 3 * heads * head_dim
+    assert _fwd(lib, d=8, heads=3, C=32, layout=1) == UNSUPPORTED      # an odd number of heads of 8: not at all
     assert _fwd(lib, d=32, heads=2, ws_bytes=1024) == WORKSPACE
     assert _fwd(lib, scales=(9,)) == UNSUPPORTED
     assert _fwd(lib, ws_bytes=1024) == WORKSPACE

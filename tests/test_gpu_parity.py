@@ -349,10 +349,12 @@ def test_forward_benchmark_configs_full_size(cfg):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("B,C,H,W,heads,d,scales", [(2, 32, 13, 37, 2, 16, (5,)), (1, 128, 70, 65, 8, 16, (3, 5)),
-                                                     (3, 80, 9, 20, 5, 16, ()), (2, 64, 21, 30, 8, 8, (5,))])
+                                                     (3, 80, 9, 20, 5, 16, ()), (2, 64, 21, 30, 8, 8, (5,)),
+                                                     (2, 64, 19, 34, 2, 32, (5,)), (1, 96, 7, 9, 1, 32, ())])
 def test_forward_channel_planar_layout(dtype, B, C, H, W, heads, d, scales):
     """x and out as [B, C, H, W]: bit for bit the token-major result, transposed (the token-major
-    result itself is checked against the oracle above).  Heads of 16 channels, and of 8 (as pairs)."""
+    result itself is checked against the oracle above).  Heads of 16 channels, of 8 (as pairs) and of 32
+    (the last case: C = 3 * heads * 32, the widest the parked result allows)."""
     print(f"forward NCHW {dtype} B={B} C={C} {H}x{W} heads={heads} head size {d} scales={scales}", flush=True)
     t = wk.random_module(77 + C + H, dtype, B, C, H, W, heads, d, scales)
     ref = run_forward(t, dtype, heads, d, scales)
