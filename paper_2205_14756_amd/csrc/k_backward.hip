@@ -11,13 +11,14 @@
 // workgroup (fixed-order sum afterwards, so results are reproducible), `backward_apply_kernel`
 // writes the three gradients.
 //
-// Every product with a state is a 16 x 16 x 16 contraction and runs on the matrix cores in fp32
+// Every product with a state's d x d part is a 16 x 16 x 16 contraction and runs on the matrix cores in fp32
 // (four v_mfma_f32_16x16x4f32 each): the operands -- tokens converted from the storage type, the
 // states as the state kernels summed them -- go in exactly, so the pass is fp32 throughout for every
 // storage type, with nothing to rescale or to split.  A wave works on 16 tokens at a time, lane
 // (token x16, q) holding channels 4q..4q+3 of its token (the fragment convention of the forward
 // kernels); a product whose contraction runs over the tokens (dS) takes its operands through a
-// multiplication with the identity, which hands lane (channel, q) the tokens 4q..4q+3 of that channel.
+// multiplication with the identity, which hands lane (channel, q) the tokens 4q..4q+3 of that channel.  What
+// involves a state's last column (the denominators, the c terms) is four vector FMAs and two cross-lane adds.
 #include "msla_device.h"
 #include "msla_kernels.h"
 
@@ -34,8 +35,8 @@ __device__ __forceinline__ f32x4 mma(f32x4 c, f32x4 a, f32x4 b) { return F32::mm
 // One state [16][17] (fp32, in memory) as matrix-core operands of this lane (x16, q):
 //   col[r]  = S[4q+r][x16]   row operand of a product contracted over the state's rows e  (out[f]  = sum_e S[e][f] x[e])
 //   row[r]  = S[x16][4q+r]   row operand of a product contracted over its columns f      (out[e]  = sum_f S[e][f] x[f])
-//   last[r] = S[4q+r][16]    the state's last column: as a row operand every output row gets sum_e S[e][16] x[e];
-//                            also the four entries that belong to the channels 4q..4q+3 this lane owns of its token
+//   last[r] = S[4q+r][16]    the state's last column, the four entries that belong to the channels 4q..4q+3 this
+//                            lane owns of its token (denominators and the "+ S[:, d] c" terms: vector FMAs)
 struct StateOperands {
     f32x4 col, row, last;
 };
