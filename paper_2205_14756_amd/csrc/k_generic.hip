@@ -135,8 +135,16 @@ __global__ __launch_bounds__(kGenThreads) void generic_state_finalize_kernel(con
     constexpr int kState = D * (D + 1);
     const long sid = blockIdx.x;
     for (int j = threadIdx.x; j < kState; j += kGenThreads) {
+        const float* p = partials + sid * nchunks * kState + j;
         float v = 0.f;
-        for (int c = 0; c < nchunks; ++c) v += partials[(sid * nchunks + c) * kState + j];     // chunk order: reproducible
+        // chunk order (reproducible); eight loads in flight at a time, a launch is otherwise one load latency a chunk
+        for (int c0 = 0; c0 < nchunks; c0 += 8) {
+            float part[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part[i] = c0 + i < nchunks ? p[(long)(c0 + i) * kState] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v += part[i];
+        }
         kv32[sid * kState + j] = v;
     }
 }
